@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the selective-recompute hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch of the 530B-class per-GPU shard
+(h=20480, a=128, t=8, s=2048, b=1: 16 heads x head_dim 160; sequence-parallel rows 256 x 20480):
+attn_core_fwd, attn_core_bwd_recompute (row pass + column pass), ln_fwd, ln_bwd, bias_dropout_add.
+`value` is the attention core's algorithmic fwd+bwd FLOPs (14 d T N, causal: T = s(s+1)/2) per second of
+whole-step time.  Per-kernel durations come from HIP events recorded between the launches of the timed
+steps, on the stream the kernels run on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="530B")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stored-steps", type=int, default=2, help="steps of the stored-activation baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2205_05198_amd as sar
+    from paper_2205_05198_amd.binding import SAR_BF16
+    from paper_2205_05198_amd.workloads import WORKLOADS, attn_inputs, rows_inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sar.load_library()   # raises if libsar.so is missing: there is no fallback path
+    w = WORKLOADS[args.workload]
+    s, b, A, d = w.s, w.b, w.A, w.d
+    N = b * A
+
+    def dev(x):
+        return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).cuda()
+
+    q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=w.seed)
+    desc = sar.AttnDesc.packed(s, b, w.a, w.h, t=w.t, rank=0, dtype=SAR_BF16, p=w.p, seed=w.seed)
+    tq, tk, tv, tdo = (dev(x) for x in (q, k, v, do))
+    o, dq, dk, dv = (torch.empty_like(tq) for _ in range(4))
+    lse = torch.empty((b, A, s), dtype=torch.float32, device="cuda")
+    ws = torch.empty(sar.attn_core_bwd_workspace(desc), dtype=torch.uint8, device="cuda")
+
+    rows, h = w.rows, w.rows_h
+    inp = rows_inputs(rows, h, "bf16", seed=w.seed)
+    rdesc = sar.RowsDesc.make(rows, h, dtype=SAR_BF16, p=w.p, seed=w.seed, offset=sar.attn_core_philox_count(desc))
+    x, resid, dy, bias, gamma, beta = (dev(inp[n]) for n in ("x", "resid", "dy", "bias", "gamma", "beta"))
+    y, dx, out = (torch.empty_like(x) for _ in range(3))
+    mean = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mean)
+    dgamma = torch.empty(h, dtype=torch.float32, device="cuda")
+    dbeta = torch.empty_like(dgamma)
+    ws2 = torch.empty(sar.ln_bwd_workspace(rdesc), dtype=torch.uint8, device="cuda")
+
+    names = ["attn_core_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "ln_fwd", "ln_bwd", "bias_dropout_add"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0)
+        sar.attn_core_fwd(desc, tq, tk, tv, o, lse)
+        mark(1)
+        sar.attn_core_bwd_recompute_dq(desc, tq, tk, tv, o, lse, tdo, dq, ws)
+        mark(2)
+        sar.attn_core_bwd_recompute_dkdv(desc, tq, tk, tv, lse, tdo, dk, dv, ws)
+        mark(3)
+        sar.ln_fwd(rdesc, x, gamma, beta, y, mean, rstd)
+        mark(4)
+        sar.ln_bwd(rdesc, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws2)
+        mark(5)
+        sar.bias_dropout_add(rdesc, x, bias, resid, out, None)
+        mark(6)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = {n: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps)])) for j, n in enumerate(names)}
+
+    # algorithmic work (causal pairs T = s(s+1)/2 per head)
+    T = s * (s + 1) // 2
+    one = 2 * d * T * N
+    flops = {"attn_core_fwd": 2 * one, "attn_bwd_dq": 3 * one, "attn_bwd_dkdv": 4 * one}   # executed contractions
+    flops_alg_fwd_bwd = 14 * d * T * N                                                      # 2 fwd + 5 bwd contractions
+    esz = 2
+    bytes_alg = {
+        "ln_fwd": rows * h * (esz + esz) + 8 * rows + 2 * esz * h,
+        "ln_bwd": rows * h * 3 * esz + 8 * rows + esz * h + 8 * h,
+        "bias_dropout_add": rows * h * 3 * esz + esz * h,
+    }
+    value = flops_alg_fwd_bwd / (ms_per_step * 1e-3) / 1e12
+    attn_ms = kern_ms["attn_core_fwd"] + kern_ms["attn_bwd_dq"] + kern_ms["attn_bwd_dkdv"]
+    dom = max(("attn_core_fwd", "attn_bwd_dq", "attn_bwd_dkdv"), key=lambda n: kern_ms[n])
+    achieved = flops[dom] / (kern_ms[dom] * 1e-3) / 1e12
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+
+    # stored-activation baseline (Section 4.1) for the recompute-vs-stored ratio
+    stored = None
+    if args.stored_steps > 0:
+        try:
+            Pst = torch.empty((b, A, s, s), dtype=torch.bfloat16, device="cuda")
+            Dst = torch.empty_like(Pst)
+            Mst = torch.empty((b, A, s, s), dtype=torch.uint8, device="cuda")
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            sar.attn_core_fwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst)
+            sar.attn_core_bwd_stored(desc, tq, tk, tv, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
+            torch.cuda.synchronize()
+            e[0].record()
+            for _ in range(args.stored_steps):
+                sar.attn_core_fwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst)
+                sar.attn_core_bwd_stored(desc, tq, tk, tv, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
+            e[1].record()
+            torch.cuda.synchronize()
+            st_ms = e[0].elapsed_time(e[1]) / args.stored_steps
+            stored = {"fwd_bwd_ms": st_ms, "recompute_over_stored": attn_ms / st_ms,
+                      "kind": "plain fp32-arithmetic kernels that write/read P, M, D (5 a s^2 b / t bytes)"}
+            del Pst, Dst, Mst
+        except Exception as ex:  # noqa: BLE001
+            stored = {"error": str(ex)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        sh = oracle.AttnShape(s=s, b=b, a=w.a, h=w.h, t=w.t, rank=0, p=w.p, seed=w.seed)
+        nthreads = oracle.num_threads()
+        nh = min(N, max(1, nthreads))
+        c0 = time.perf_counter()
+        oracle.attn_fwd(sh, q, k, v, heads=(0, nh))
+        oracle.attn_bwd(sh, q, k, v, do, heads=(0, nh))
+        oracle.ln_fwd(inp["x"], inp["gamma"], inp["beta"])
+        oracle.ln_bwd(inp["dy"], inp["x"], inp["gamma"])
+        oracle.bias_dropout_add(inp["x"], inp["bias"], inp["resid"], w.p, w.seed, 0)
+        c1 = time.perf_counter()
+        cpu = {"value": 14 * d * T * nh / (c1 - c0) / 1e12, "unit": "TFLOP/s", "cores": min(nthreads, nh), "kind": "oracle",
+               "sample": f"{nh} of {N} heads of the {args.workload} attention core fwd+bwd (fp64, OpenMP over heads) + full LayerNorm fwd/bwd + "
+                         f"bias-dropout-add, {c1 - c0:.1f} s", "seconds": c1 - c0}
+
+    line = {
+        "metric": "selective-recompute attn fwd+bwd TFLOP/s (% MFMA peak) at 1 GPU",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}-class per-GPU shard: attention core b={b} s={s} heads={A} head_dim={d} causal p={w.p}; "
+                               f"LayerNorm fwd/bwd + bias-dropout-add on {rows}x{h} bf16", "t": w.t},
+        "pct_mfma_peak": 100.0 * value / PEAK_BF16_MFMA_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic},
+        "cpu_baseline": cpu,
+        "kernels_ms": kern_ms,
+        "attn_fwd_bwd": {"ms": attn_ms, "tflops_algorithmic_14dTN": flops_alg_fwd_bwd / (attn_ms * 1e-3) / 1e12,
+                         "tflops_model_12dTN": 12 * d * T * N / (attn_ms * 1e-3) / 1e12,
+                         "tflops_executed_18dTN": 18 * d * T * N / (attn_ms * 1e-3) / 1e12},
+        "rows_kernels_gbs": {n: bytes_alg[n] / (kern_ms[n] * 1e-3) / 1e9 for n in bytes_alg},
+        "rows_kernels_frac_hbm_peak": {n: bytes_alg[n] / (kern_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS for n in bytes_alg},
+        "stored_baseline": stored,
+        "paper_context": {"full_recompute_overhead_pct": "30-40", "mfu_530B_2240_A100_pct": 54.2},
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

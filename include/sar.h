@@ -1,0 +1,186 @@
+/*
+ * sar.h -- C ABI of the selective-activation-recomputation hot path for MI355X (gfx950).
+ *
+ * Method: "Reducing Activation Recomputation in Large Transformer Models" (arXiv 2205.05198).
+ * The library implements, as hand-written HIP kernels,
+ *   - the attention core that Section 5 selects for recomputation (QK^T, softmax, softmax dropout,
+ *     attention over V; Section 4.1), in a form whose forward keeps only Q, K, V, O and a per-row
+ *     log-sum-exp and whose backward regenerates softmax and the dropout mask on the fly, and
+ *   - the memory-bound operators of the sequence-parallel region (Section 4.2.2, Eq. 3): LayerNorm
+ *     forward/backward and dropout(+bias)+residual on one rank's s/t rows.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or synchronises: each call validates its arguments on the host, enqueues its kernels on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and returns.
+ *   - Return value: SAR_OK or a negative sar_status.  On any non-OK return nothing has been
+ *     enqueued and no output byte is written; sar_last_error() gives a thread-local description.
+ *   - Names follow the paper's Table 1: s sequence length, b microbatch, h hidden size, a attention
+ *     heads, t tensor-parallel size; p is the dropout probability here (the paper's pipeline size
+ *     does not appear in this library).
+ *   - Attention tensors are the paper's s x b x h activations seen by one tensor-parallel rank:
+ *     [s, b, A, d] with A = a/t local heads and d = h/a, d contiguous, element strides given in the
+ *     descriptor.  Q, K, V, O and all gradients share the same strides.
+ *   - Dropout masks are a pure function of (seed, offset, global element index): Philox4x32-10,
+ *     key = seed, counter = (G lo, G hi, 0, site) with G = offset + (e >> 3); element e uses the
+ *     16-bit field (e & 7) of the 128 output bits and is kept iff field >= floor(p*65536 + 0.5).
+ *     Site 0 (softmax dropout): e = ((beta*a + rank*A + n)*s + i)*s + j.  Site 1 (bias-dropout-add):
+ *     e = (row_offset + r)*h + c.  A shard therefore reproduces its slice of the unsharded mask.
+ *   - Supported shapes: d in {64, 96, 128, 160} for bf16 (any multiple of 4 up to 256 for f32);
+ *     s % 8 == 0; a % t == 0; h % a == 0; rows-kernels need h % 8 == 0 and h <= 32768.  Base pointers and
+ *     row strides must be 16-byte aligned.  Anything else returns SAR_ERR_UNSUPPORTED / SAR_ERR_ALIGN.
+ */
+#ifndef SAR_H_
+#define SAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SAR_OK = 0,
+  SAR_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  SAR_ERR_SHAPE = -2,       /* a size is non-positive or inconsistent (a % t, h % a, ...)   */
+  SAR_ERR_UNSUPPORTED = -3, /* a shape or option the kernels do not cover                   */
+  SAR_ERR_ALIGN = -4,       /* pointer or stride not 16-byte aligned                        */
+  SAR_ERR_PROB = -5,        /* dropout probability outside [0, 1)                           */
+  SAR_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than *_workspace() reports         */
+  SAR_ERR_HIP = -7          /* a HIP runtime call failed (launch error)                     */
+} sar_status;
+
+typedef enum { SAR_F32 = 0, SAR_BF16 = 1 } sar_dtype;
+
+/* Attention-core descriptor (paper notation, Table 1). */
+typedef struct {
+  int32_t s, b;            /* sequence length, microbatch                                          */
+  int32_t a, t, rank;      /* global heads, tensor-parallel size, this GPU's rank in [0, t):
+                              local head n has global index rank*(a/t) + n (used by Philox only)  */
+  int32_t h;               /* hidden size; head dimension d = h / a                                */
+  int32_t dtype;           /* sar_dtype of Q, K, V, O, dO, dQ, dK, dV                              */
+  int32_t causal;          /* must be 1 (decoder mask, keys j <= i)                                */
+  float scale;             /* alpha applied to QK^T; pass 1/sqrt(d)                                */
+  float p;                 /* softmax-dropout probability, 0 <= p < 1                              */
+  uint64_t seed, offset;   /* Philox key and counter base                                          */
+  int64_t stride_s, stride_b, stride_a; /* element strides of [s, b, A, d]; packed layout:
+                              stride_a = d, stride_b = A*d, stride_s = b*A*d                       */
+} sar_attn_desc;
+
+/*
+ * attn_core_fwd -- Section 4.1 (QK^T, softmax, softmax dropout, attention over V) computed as in
+ * Section 5: nothing of size s x s is written.
+ *   q, k, v : in,  device, [s, b, A, d] in desc->dtype
+ *   o       : out, device, same layout; O = (softmax(alpha QK^T, causal) o M / (1-p)) V
+ *   lse     : out, device, float [b, A, s]; natural-log-sum-exp of row i's scaled scores
+ * Saved set for the backward = {q, k, v, o, lse, seed, offset}.
+ */
+sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                         void* o, float* lse, void* stream);
+
+/* Bytes of scratch attn_core_bwd_recompute needs for this descriptor (0 on error). */
+size_t attn_core_bwd_workspace(const sar_attn_desc* desc);
+
+/*
+ * attn_core_bwd_recompute -- backward of the region of Section 5: softmax P and the dropout mask are
+ * regenerated from q, k, lse and (seed, offset); dq, dk, dv follow the chain rule through
+ * Section 4.1's four operations.
+ *   q, k, v, o, lse : in, exactly what attn_core_fwd received / produced
+ *   d_o             : in, gradient of o, same layout and dtype
+ *   dq, dk, dv      : out, same layout and dtype (may not alias inputs or each other)
+ *   workspace       : device scratch of at least attn_core_bwd_workspace(desc) bytes, 16-byte
+ *                     aligned; contents on entry are irrelevant, contents on exit unspecified
+ * Results are deterministic (no atomics).
+ */
+sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                   const void* o, const float* lse, const void* d_o,
+                                   void* dq, void* dk, void* dv,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two passes of attn_core_bwd_recompute as separate calls (same kernels, same arguments): the row
+ * pass recomputes the region per query block and writes dq and the per-row term sum_k dO_ik O_ik into the
+ * workspace; the column pass recomputes it per key block, reads that term back and writes dk, dv.
+ * Row pass then column pass on one stream, with the same workspace, equals attn_core_bwd_recompute.
+ */
+sar_status attn_core_bwd_recompute_dq(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                      const void* o, const float* lse, const void* d_o, void* dq,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+sar_status attn_core_bwd_recompute_dkdv(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                        const float* lse, const void* d_o, void* dk, void* dv,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Stored-activation baseline (what Section 4.1 itemises and Section 5 avoids): the forward also
+ * writes the softmax output P, the dropout mask M and the dropout output D, and the backward reads
+ * them back instead of recomputing.  Used for the recompute-vs-stored timing ratio and to expose the
+ * mask bit for bit.
+ *   P, D : desc->dtype [b, A, s, s];  M : uint8 [b, A, s, s]; entries with j > i are written as 0.
+ * Exactly (2*elem + 1) * A * s^2 * b extra bytes = the paper's 5 a s^2 b / t for 16-bit elements.
+ * attn_core_bwd_stored takes the same workspace as attn_core_bwd_recompute (per-row softmax term).
+ */
+sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                void* o, void* P, uint8_t* M, void* D, void* stream);
+sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                const void* P, const uint8_t* M, const void* D, const void* d_o,
+                                void* dq, void* dk, void* dv,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes held from forward to backward by the attention core on this rank: Q, K, V, O and, when
+ * selective == 0, the three s x s tensors (Section 4.1; Table 2 rows with / without selective
+ * recomputation).  The fp32 log-sum-exp and the 16 bytes of (seed, offset) are "small buffers" in the
+ * paper's sense and are reported by attn_core_small_buffer_bytes.  0 on an invalid descriptor. */
+uint64_t attn_core_saved_bytes(const sar_attn_desc* desc, int selective);
+uint64_t attn_core_small_buffer_bytes(const sar_attn_desc* desc);
+
+/* Number of Philox calls one attention call may consume (b*a*s*s/8, the global score tensor, so
+ * ranks need not coordinate); advance `offset` by at least this between calls. */
+uint64_t attn_core_philox_count(const sar_attn_desc* desc);
+
+/* Rows descriptor for the sequence-parallel region: rows = (s/t)*b local rows of width h. */
+typedef struct {
+  int64_t rows, h;
+  int64_t row_offset;      /* global index of local row 0 = rank*(s/t)*b (feeds Philox only)  */
+  int32_t dtype;           /* sar_dtype of x, y, dy, dx, resid, out, gamma, beta, bias         */
+  float eps;               /* LayerNorm epsilon (1e-5)                                         */
+  float p;                 /* dropout probability of bias_dropout_add, 0 <= p < 1              */
+  uint64_t seed, offset;   /* Philox key and counter base of bias_dropout_add                  */
+} sar_rows_desc;
+
+/*
+ * ln_fwd -- LayerNorm of Eq. 3's first line on this rank's rows: per row mu, biased variance,
+ * rstd = 1/sqrt(var + eps), y = (x - mu) rstd gamma + beta.
+ *   x [rows, h], gamma [h], beta [h] : in, desc->dtype;  y [rows, h] : out, desc->dtype
+ *   mean [rows], rstd [rows] : out, float (the "small buffers" of Section 4)
+ */
+sar_status ln_fwd(const sar_rows_desc* desc, const void* x, const void* gamma, const void* beta,
+                  void* y, float* mean, float* rstd, void* stream);
+
+/* Bytes of scratch ln_bwd needs (per-workgroup partial sums of dgamma / dbeta). */
+size_t ln_bwd_workspace(const sar_rows_desc* desc);
+
+/*
+ * ln_bwd -- gradient of ln_fwd.  dx in desc->dtype; dgamma, dbeta are float [h], summed over this
+ * rank's rows only (the sum over ranks is the caller's all-reduce).
+ */
+sar_status ln_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const float* mean, const float* rstd,
+                  const void* gamma, void* dx, float* dgamma, float* dbeta,
+                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * bias_dropout_add -- last line of Eq. 3 plus the residual connection:
+ *   out = resid + M o (x + bias) / (1 - p),  M from Philox site 1.
+ *   bias [h] may be NULL (the paper's Dropout(W)); mask_out uint8 [rows, h] may be NULL (the paper
+ *   stores this mask, sbh bytes; Philox can regenerate it); out may alias resid (in-place residual).
+ */
+sar_status bias_dropout_add(const sar_rows_desc* desc, const void* x, const void* bias, const void* resid,
+                            void* out, uint8_t* mask_out, void* stream);
+
+/* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
+const char* sar_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAR_H_ */

@@ -141,17 +141,18 @@ def attn_fwd(sh: AttnShape, q, k, v, materialise: bool = False, heads=None):
     """Returns dict(o [s,b,A,d], lse [b,A,s], and with materialise: P, M, D [b,A,s,s]).
 
     ``heads`` = (lo, hi) restricts the work to flattened (batch*A + head) indices in [lo, hi); the
-    other entries of the outputs stay zero."""
+    other entries of o and lse stay zero, and P, M, D then have shape [hi-lo, s, s]."""
     q, k, v = _f64(q), _f64(k), _f64(v)
     assert q.shape == (sh.s, sh.b, sh.A, sh.d) == k.shape == v.shape
     o = np.zeros_like(q)
     lse = np.zeros((sh.b, sh.A, sh.s), dtype=np.float64)
     P = M = D = None
+    lo, hi = heads if heads is not None else (0, sh.b * sh.A)
     if materialise:
-        P = np.zeros((sh.b, sh.A, sh.s, sh.s), dtype=np.float64)
+        shape = (sh.b, sh.A, sh.s, sh.s) if heads is None else (hi - lo, sh.s, sh.s)
+        P = np.zeros(shape, dtype=np.float64)
         D = np.zeros_like(P)
         M = np.zeros(P.shape, dtype=np.uint8)
-    lo, hi = heads if heads is not None else (0, sh.b * sh.A)
     d = sh._c()
     rc = lib().orc_attn_fwd(ctypes.byref(d), _dp(q), _dp(k), _dp(v), _dp(o), _dp(lse), _dp(P), _dp(M), _dp(D),
                             ctypes.c_int(lo), ctypes.c_int(hi))
@@ -169,10 +170,10 @@ def attn_bwd(sh: AttnShape, q, k, v, dO, extras: bool = False, heads=None):
     assert q.shape == (sh.s, sh.b, sh.A, sh.d) == k.shape == v.shape == dO.shape
     dq, dk, dv = np.zeros_like(q), np.zeros_like(q), np.zeros_like(q)
     delta = dS = None
+    lo, hi = heads if heads is not None else (0, sh.b * sh.A)
     if extras:
         delta = np.zeros((sh.b, sh.A, sh.s), dtype=np.float64)
-        dS = np.zeros((sh.b, sh.A, sh.s, sh.s), dtype=np.float64)
-    lo, hi = heads if heads is not None else (0, sh.b * sh.A)
+        dS = np.zeros((sh.b, sh.A, sh.s, sh.s) if heads is None else (hi - lo, sh.s, sh.s), dtype=np.float64)
     d = sh._c()
     rc = lib().orc_attn_bwd(ctypes.byref(d), _dp(q), _dp(k), _dp(v), _dp(dO), _dp(dq), _dp(dk), _dp(dv), _dp(delta), _dp(dS),
                             ctypes.c_int(lo), ctypes.c_int(hi))

@@ -132,7 +132,7 @@ uint64_t orc_attn_philox_count(const orc_attn_desc* c) {
  *      LSE_i = m_i + ln l_i
  *   4. D_ij = P_ij * M_ij / (1 - p)              (inverted dropout on the normalised P)
  *   5. O_ik = sum_j D_ij V_jk
- * Optional outputs (may be NULL): P, D as double [b][A][s][s], M as bytes (0 above the
+ * Optional outputs (may be NULL): P, D as double [head_hi - head_lo][s][s], M as bytes (0 above the
  * diagonal when causal) -- the tensors the non-selective path would have to store.
  * ------------------------------------------------------------------------------------- */
 int orc_attn_fwd(const orc_attn_desc* c, const double* q, const double* k, const double* v,
@@ -184,9 +184,9 @@ int orc_attn_fwd(const orc_attn_desc* c, const double* q, const double* k, const
         for (int x = 0; x < d; ++x) oi[x] += D[(size_t)i * s + j] * vj[x];
       }
     }
-    if (Pout) memcpy(Pout + (size_t)bn * s * s, P, (size_t)s * s * sizeof(double));
-    if (Dout) memcpy(Dout + (size_t)bn * s * s, D, (size_t)s * s * sizeof(double));
-    if (Mout) memcpy(Mout + (size_t)bn * s * s, M, (size_t)s * s);
+    if (Pout) memcpy(Pout + (size_t)(bn - head_lo) * s * s, P, (size_t)s * s * sizeof(double));
+    if (Dout) memcpy(Dout + (size_t)(bn - head_lo) * s * s, D, (size_t)s * s * sizeof(double));
+    if (Mout) memcpy(Mout + (size_t)(bn - head_lo) * s * s, M, (size_t)s * s);
     free(S); free(P); free(D); free(M);
   }
   return failed ? -1 : 0;
@@ -198,7 +198,7 @@ int orc_attn_fwd(const orc_attn_desc* c, const double* q, const double* k, const
  *   dD_ij = sum_k dO_ik V_jk        dP_ij = dD_ij * M_ij / (1-p)
  *   delta_i = sum_j P_ij dP_ij      dS_ij = P_ij (dP_ij - delta_i)
  *   dV_jk = sum_i D_ij dO_ik        dQ_ik = alpha sum_j dS_ij K_jk     dK_jk = alpha sum_i dS_ij Q_ik
- * Optional outputs: delta [b][A][s], dS [b][A][s][s] (for the invariant tests).
+ * Optional outputs: delta [b][A][s], dS [head_hi - head_lo][s][s] (for the invariant tests).
  * ------------------------------------------------------------------------------------- */
 int orc_attn_bwd(const orc_attn_desc* c, const double* q, const double* k, const double* v, const double* dO,
                  double* dq, double* dk, double* dv, double* delta_out, double* dS_out,
@@ -276,7 +276,7 @@ int orc_attn_bwd(const orc_attn_desc* c, const double* q, const double* k, const
       }
       for (int x = 0; x < d; ++x) dkj[x] *= alpha;
     }
-    if (dS_out) memcpy(dS_out + (size_t)bn * s * s, dS, (size_t)s * s * sizeof(double));
+    if (dS_out) memcpy(dS_out + (size_t)(bn - head_lo) * s * s, dS, (size_t)s * s * sizeof(double));
     free(P); free(dS); free(Mk); free(row);
   }
   return failed ? -1 : 0;

@@ -1,0 +1,335 @@
+// Memory-bound operators of the sequence-parallel region (Section 4.2.2, Eq. 3) on one rank's rows:
+// LayerNorm forward / backward and dropout(+bias)+residual.  One pass over HBM per tensor, 128-bit accesses.
+#include "sar_device.h"
+#include "sar_internal.h"
+
+namespace sar {
+
+// 8 consecutive elements (one 16-byte access for bf16, two for fp32) <-> 8 floats
+template <typename T> struct Vec8;
+template <> struct Vec8<uint16_t> {
+  static __device__ __forceinline__ void load(const uint16_t* p, float (&f)[8]) {
+    uint4 u = *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      f[2 * e] = __uint_as_float(w[e] << 16);
+      f[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+  static __device__ __forceinline__ void store(uint16_t* p, const float (&f)[8]) {
+    uint4 u;
+    u.x = pack_bf16x2(f[0], f[1]);
+    u.y = pack_bf16x2(f[2], f[3]);
+    u.z = pack_bf16x2(f[4], f[5]);
+    u.w = pack_bf16x2(f[6], f[7]);
+    *reinterpret_cast<uint4*>(p) = u;
+  }
+};
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&f)[8]) {
+    float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&f)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(f[0], f[1], f[2], f[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(f[4], f[5], f[6], f[7]);
+  }
+};
+
+// block-wide sum of two values; every thread gets the totals.  red must hold 2 * 16 floats.
+__device__ __forceinline__ void block_sum2(float& a, float& b, float* red) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = (blockDim.x + 63) >> 6;
+  if (lane == 0) { red[wave] = a; red[16 + wave] = b; }
+  __syncthreads();
+  float ta = 0.f, tb = 0.f;
+  for (int w = 0; w < nw; ++w) { ta += red[w]; tb += red[16 + w]; }
+  a = ta;
+  b = tb;
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LayerNorm forward: one workgroup per row, the row lives in registers (VPT chunks of 8 per thread).
+// Statistics in fp32 with the row's first element as shift, so one reduction gives mean and variance.
+// ---------------------------------------------------------------------------------------------------
+template <typename T, int VPT>
+__global__ __launch_bounds__(1024) void ln_fwd_kernel(RowsParams P, const T* __restrict__ x, const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                     T* __restrict__ y, float* __restrict__ mean, float* __restrict__ rstd) {
+  __shared__ float red[32];
+  const int64_t r = blockIdx.x;
+  const int nchunk = (int)(P.h >> 3);
+  const T* xr = x + r * P.h;
+  float xv[VPT][8];
+  const float shift = Elem<T>::load(xr);
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+      Vec8<T>::load(xr + 8 * c, xv[u]);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float dlt = xv[u][e] - shift;
+        s1 += dlt;
+        s2 = fmaf(dlt, dlt, s2);
+      }
+    }
+  }
+  block_sum2(s1, s2, red);
+  const float invh = 1.f / (float)P.h;
+  const float m1 = s1 * invh;
+  const float var = fmaxf(s2 * invh - m1 * m1, 0.f);
+  const float mu = shift + m1;
+  const float rs = rsqrtf(var + P.eps);
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+      float g[8], bt[8], out[8];
+      Vec8<T>::load(gamma + 8 * c, g);
+      Vec8<T>::load(beta + 8 * c, bt);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) out[e] = fmaf((xv[u][e] - mu) * rs, g[e], bt[e]);
+      Vec8<T>::store(y + r * P.h + 8 * c, out);
+    }
+  }
+  if (threadIdx.x == 0) { mean[r] = mu; rstd[r] = rs; }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LayerNorm backward, pass 1: per row c1 = mean_c(g), c2 = mean_c(g xhat) with g = dy*gamma.
+// ---------------------------------------------------------------------------------------------------
+template <typename T, int VPT>
+__global__ __launch_bounds__(1024) void ln_bwd_rowstats_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
+                                                              const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                              const T* __restrict__ gamma, float2* __restrict__ rowstat) {
+  __shared__ float red[32];
+  const int64_t r = blockIdx.x;
+  const int nchunk = (int)(P.h >> 3);
+  const float mu = mean[r], rs = rstd[r];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+      float xv[8], dv[8], g[8];
+      Vec8<T>::load(x + r * P.h + 8 * c, xv);
+      Vec8<T>::load(dy + r * P.h + 8 * c, dv);
+      Vec8<T>::load(gamma + 8 * c, g);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float gg = dv[e] * g[e];
+        s1 += gg;
+        s2 = fmaf(gg, (xv[e] - mu) * rs, s2);
+      }
+    }
+  }
+  block_sum2(s1, s2, red);
+  if (threadIdx.x == 0) rowstat[r] = make_float2(s1 / (float)P.h, s2 / (float)P.h);
+}
+
+// ---------------------------------------------------------------------------------------------------
+// LayerNorm backward, pass 2: a workgroup owns a slab of 64 columns and a contiguous range of rows.
+// 8 lanes cover one row segment (64 columns), 32 row segments per step.  dx is written in place of the
+// row formula; dgamma / dbeta of the slab are summed over the workgroup's rows in registers, then in LDS.
+// part[split][0][h] = dgamma partial, part[split][1][h] = dbeta partial (or the final arrays if 1 split).
+// ---------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ln_bwd_slab_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
+                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                         const T* __restrict__ gamma, const float2* __restrict__ rowstat, T* __restrict__ dx,
+                                                         float* __restrict__ dg_out, float* __restrict__ db_out, int rows_per_split) {
+  __shared__ float sg[32][65], sb[32][65];
+  const int slab = blockIdx.x, split = blockIdx.y;
+  const int seg = threadIdx.x >> 3, l8 = threadIdx.x & 7;
+  const int64_t col = (int64_t)slab * 64 + 8 * l8;
+  const bool colok = col < P.h;
+  const int64_t r_lo = (int64_t)split * rows_per_split;
+  const int64_t r_hi = min(P.rows, r_lo + rows_per_split);
+  float g[8], ag[8], ab[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { ag[e] = 0.f; ab[e] = 0.f; g[e] = 0.f; }
+  if (colok) Vec8<T>::load(gamma + col, g);
+  for (int64_t r = r_lo + seg; r < r_hi; r += 32) {
+    if (colok) {
+      float xv[8], dv[8], out[8];
+      Vec8<T>::load(x + r * P.h + col, xv);
+      Vec8<T>::load(dy + r * P.h + col, dv);
+      const float mu = mean[r], rs = rstd[r];
+      const float2 st = rowstat[r];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float xh = (xv[e] - mu) * rs;
+        float gg = dv[e] * g[e];
+        out[e] = rs * (gg - st.x - xh * st.y);
+        ag[e] = fmaf(dv[e], xh, ag[e]);
+        ab[e] += dv[e];
+      }
+      Vec8<T>::store(dx + r * P.h + col, out);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { sg[seg][8 * l8 + e] = ag[e]; sb[seg][8 * l8 + e] = ab[e]; }
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    const int c = threadIdx.x & 63;
+    const bool isb = threadIdx.x >= 64;
+    float t = 0.f;
+    for (int q = 0; q < 32; ++q) t += isb ? sb[q][c] : sg[q][c];
+    const int64_t cc = (int64_t)slab * 64 + c;
+    if (cc < P.h) {
+      float* dst = isb ? db_out : dg_out;
+      dst[(size_t)split * 2 * P.h + cc] = t;
+    }
+  }
+}
+
+// sums the row-split partials: part[nsplit][2][h] -> dgamma[h], dbeta[h]
+__global__ void ln_bwd_finish_kernel(const float* __restrict__ part, int nsplit, int64_t h, float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= h) return;
+  float tg = 0.f, tb = 0.f;
+  for (int q = 0; q < nsplit; ++q) {
+    tg += part[(size_t)q * 2 * h + c];
+    tb += part[(size_t)q * 2 * h + h + c];
+  }
+  dgamma[c] = tg;
+  dbeta[c] = tb;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bias-dropout-add: out = resid + M (x + bias) / (1-p); one thread per 8 elements = one Philox call.
+// ---------------------------------------------------------------------------------------------------
+template <typename T, bool HAS_BIAS, bool HAS_MASK>
+__global__ __launch_bounds__(256) void bias_dropout_add_kernel(RowsParams P, const T* __restrict__ x, const T* __restrict__ bias, const T* resid,
+                                                              T* out, uint8_t* __restrict__ mask) {
+  const int64_t nchunk_row = P.h >> 3;
+  const int64_t total = P.rows * nchunk_row;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
+  float xv[8], rv[8], bv[8], o[8];
+  Vec8<T>::load(x + r * P.h + c, xv);
+  Vec8<T>::load(resid + r * P.h + c, rv);
+  if (HAS_BIAS) Vec8<T>::load(bias + c, bv);
+  const uint64_t e = (uint64_t)(P.row_offset + r) * (uint64_t)P.h + (uint64_t)c;
+  const uint32_t keep = keep_bits8(P.offset + (e >> 3), 1u, P.key0, P.key1, P.thresh);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    float xb = HAS_BIAS ? xv[q] + bv[q] : xv[q];
+    o[q] = ((keep >> q) & 1u) ? fmaf(xb, P.keep_scale, rv[q]) : rv[q];
+  }
+  Vec8<T>::store(out + r * P.h + c, o);
+  if (HAS_MASK) {
+    uint2 m;
+    m.x = (keep & 1u) | ((keep & 2u) << 7) | ((keep & 4u) << 14) | ((keep & 8u) << 21);
+    m.y = ((keep >> 4) & 1u) | ((keep & 32u) << 3) | ((keep & 64u) << 10) | ((keep & 128u) << 17);
+    *reinterpret_cast<uint2*>(mask + r * P.h + c) = m;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ launchers
+static inline int pick_vpt(int64_t h, int& threads) {
+  const int nchunk = (int)(h >> 3);
+  int vpt = (nchunk + 1023) / 1024;
+  if (vpt < 1) vpt = 1;
+  threads = (nchunk + vpt - 1) / vpt;
+  threads = (threads + 63) / 64 * 64;
+  return vpt;
+}
+
+template <typename T>
+static hipError_t ln_fwd_t(const RowsParams& P, const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd, hipStream_t st) {
+  int threads;
+  const int vpt = pick_vpt(P.h, threads);
+  dim3 grid((unsigned)P.rows), block(threads);
+#define SAR_LN_FWD(V) hipLaunchKernelGGL((ln_fwd_kernel<T, V>), grid, block, 0, st, P, (const T*)x, (const T*)gamma, (const T*)beta, (T*)y, mean, rstd)
+  switch (vpt) {
+    case 1: SAR_LN_FWD(1); break;
+    case 2: SAR_LN_FWD(2); break;
+    case 3: SAR_LN_FWD(3); break;
+    default: SAR_LN_FWD(4); break;
+  }
+#undef SAR_LN_FWD
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
+                         hipStream_t st) {
+  return bf16 ? ln_fwd_t<uint16_t>(P, x, gamma, beta, y, mean, rstd, st) : ln_fwd_t<float>(P, x, gamma, beta, y, mean, rstd, st);
+}
+
+static inline void ln_bwd_plan(int64_t rows, int64_t h, int& nslab, int& nsplit, int& rows_per_split) {
+  nslab = (int)((h + 63) / 64);
+  int want = (1024 + nslab - 1) / nslab;                 // aim at >= 1024 workgroups
+  int maxsplit = (int)((rows + 31) / 32);                 // at least one 32-row step per split
+  nsplit = want < 1 ? 1 : (want > maxsplit ? maxsplit : want);
+  if (nsplit < 1) nsplit = 1;
+  rows_per_split = (int)((rows + nsplit - 1) / nsplit);
+  nsplit = (int)((rows + rows_per_split - 1) / rows_per_split);
+}
+
+size_t ln_bwd_workspace_bytes(int64_t rows, int64_t h) {
+  int nslab, nsplit, rps;
+  ln_bwd_plan(rows, h, nslab, nsplit, rps);
+  size_t rowstat = ((size_t)rows * sizeof(float2) + 255) / 256 * 256;
+  return rowstat + (size_t)nsplit * 2 * (size_t)h * sizeof(float);
+}
+
+template <typename T>
+static hipError_t ln_bwd_t(const RowsParams& P, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
+                           float* dgamma, float* dbeta, void* ws, hipStream_t st) {
+  int nslab, nsplit, rps;
+  ln_bwd_plan(P.rows, P.h, nslab, nsplit, rps);
+  float2* rowstat = (float2*)ws;
+  float* part = (float*)((char*)ws + ((size_t)P.rows * sizeof(float2) + 255) / 256 * 256);
+  int threads;
+  const int vpt = pick_vpt(P.h, threads);
+  dim3 grid((unsigned)P.rows), block(threads);
+#define SAR_LN_RS(V) hipLaunchKernelGGL((ln_bwd_rowstats_kernel<T, V>), grid, block, 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, rowstat)
+  switch (vpt) {
+    case 1: SAR_LN_RS(1); break;
+    case 2: SAR_LN_RS(2); break;
+    case 3: SAR_LN_RS(3); break;
+    default: SAR_LN_RS(4); break;
+  }
+#undef SAR_LN_RS
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // partial layout [split][2][h]: dgamma part at +0, dbeta part at +h
+  hipLaunchKernelGGL((ln_bwd_slab_kernel<T>), dim3(nslab, nsplit), dim3(256), 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma,
+                     (const float2*)rowstat, (T*)dx, part, part + P.h, rps);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(ln_bwd_finish_kernel, dim3((unsigned)((P.h + 255) / 256)), dim3(256), 0, st, (const float*)part, nsplit, P.h, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_bwd(const RowsParams& P, bool bf16, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
+                         void* dx, float* dgamma, float* dbeta, void* ws, hipStream_t st) {
+  return bf16 ? ln_bwd_t<uint16_t>(P, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws, st)
+              : ln_bwd_t<float>(P, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws, st);
+}
+
+template <typename T>
+static hipError_t bda_t(const RowsParams& P, const void* x, const void* bias, const void* resid, void* out, uint8_t* mask, hipStream_t st) {
+  const int64_t total = P.rows * (P.h >> 3);
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+#define SAR_BDA(B, M) hipLaunchKernelGGL((bias_dropout_add_kernel<T, B, M>), grid, block, 0, st, P, (const T*)x, (const T*)bias, (const T*)resid, (T*)out, mask)
+  if (bias && mask) SAR_BDA(true, true);
+  else if (bias) SAR_BDA(true, false);
+  else if (mask) SAR_BDA(false, true);
+  else SAR_BDA(false, false);
+#undef SAR_BDA
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_dropout_add(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, void* out, uint8_t* mask,
+                                   hipStream_t st) {
+  return bf16 ? bda_t<uint16_t>(P, x, bias, resid, out, mask, st) : bda_t<float>(P, x, bias, resid, out, mask, st);
+}
+
+}  // namespace sar

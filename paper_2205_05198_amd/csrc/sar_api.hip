@@ -1,0 +1,256 @@
+// C-ABI layer of libsar: argument validation on the host, then kernel launches on the caller's stream.
+// See include/sar.h for the contract of every entry point.
+#include "../../include/sar.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "sar_internal.h"
+
+namespace {
+
+thread_local char g_err[256] = "";
+
+sar_status fail(sar_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Dropout threshold on 16 random bits: floor(p * 65536 + 0.5) from the float p.
+inline uint32_t dropout_threshold(float p) { return (uint32_t)std::floor((double)p * 65536.0 + 0.5); }
+
+sar_status check_attn_desc(const sar_attn_desc* c, sar::AttnParams* P) {
+  if (!c) return fail(SAR_ERR_NULL, "descriptor is NULL");
+  if (c->s <= 0 || c->b <= 0 || c->a <= 0 || c->t <= 0 || c->h <= 0) return fail(SAR_ERR_SHAPE, "s, b, a, t, h must be positive");
+  if (c->a % c->t != 0) return fail(SAR_ERR_SHAPE, "a (%d) is not a multiple of t (%d)", c->a, c->t);
+  if (c->h % c->a != 0) return fail(SAR_ERR_SHAPE, "h (%d) is not a multiple of a (%d)", c->h, c->a);
+  if (c->rank < 0 || c->rank >= c->t) return fail(SAR_ERR_SHAPE, "rank %d outside [0, t)", c->rank);
+  if (c->dtype != SAR_F32 && c->dtype != SAR_BF16) return fail(SAR_ERR_UNSUPPORTED, "dtype %d", c->dtype);
+  if (c->causal != 1) return fail(SAR_ERR_UNSUPPORTED, "only the causal core is built (causal = %d)", c->causal);
+  if (!(c->p >= 0.f && c->p < 1.f)) return fail(SAR_ERR_PROB, "dropout probability %g outside [0, 1)", (double)c->p);
+  if (!std::isfinite(c->scale)) return fail(SAR_ERR_SHAPE, "scale is not finite");
+  const int d = c->h / c->a, A = c->a / c->t;
+  if (c->s % 8 != 0) return fail(SAR_ERR_UNSUPPORTED, "s (%d) must be a multiple of 8", c->s);
+  if (c->s > 32768) return fail(SAR_ERR_UNSUPPORTED, "s (%d) above 32768", c->s);
+  if (d % 4 != 0 || d > 256) return fail(SAR_ERR_UNSUPPORTED, "head dimension %d (need a multiple of 4, at most 256)", d);
+  if (c->dtype == SAR_BF16 && d % 8 != 0) return fail(SAR_ERR_UNSUPPORTED, "bf16 head dimension %d must be a multiple of 8", d);
+  const int64_t esz = c->dtype == SAR_BF16 ? 2 : 4;
+  if (c->stride_a < d || c->stride_b < 0 || c->stride_s < 0) return fail(SAR_ERR_SHAPE, "strides must be non-negative and stride_a >= d");
+  if ((c->stride_s * esz) % 16 || (c->stride_b * esz) % 16 || (c->stride_a * esz) % 16) return fail(SAR_ERR_ALIGN, "strides must be multiples of 16 bytes");
+  if ((int64_t)c->b * A > 65535) return fail(SAR_ERR_UNSUPPORTED, "b * a/t above 65535");
+  if (P) {
+    P->s = c->s; P->b = c->b; P->A = A; P->d = d;
+    P->a_global = c->a; P->head0 = c->rank * A;
+    P->stride_s = c->stride_s; P->stride_b = c->stride_b; P->stride_a = c->stride_a;
+    P->scale = c->scale; P->p = c->p; P->keep_scale = 1.0f / (1.0f - c->p);
+    P->thresh = dropout_threshold(c->p);
+    P->key0 = (uint32_t)(c->seed & 0xFFFFFFFFu); P->key1 = (uint32_t)(c->seed >> 32);
+    P->offset = c->offset;
+  }
+  return SAR_OK;
+}
+
+bool use_mfma(const sar_attn_desc* c, const sar::AttnParams& P) { return c->dtype == SAR_BF16 && sar::attn_mfma_supported(P.d); }
+
+sar_status check_simple_limits(const sar::AttnParams& P) {
+  if (sar::attn_simple_lds_bytes(P.s) > 160 * 1024) return fail(SAR_ERR_UNSUPPORTED, "s (%d) too long for this dtype / head dimension", P.s);
+  return SAR_OK;
+}
+
+sar_status hip_fail(hipError_t e, const char* what) { return fail(SAR_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
+
+sar_status check_rows_desc(const sar_rows_desc* c, sar::RowsParams* P) {
+  if (!c) return fail(SAR_ERR_NULL, "descriptor is NULL");
+  if (c->rows <= 0 || c->h <= 0 || c->row_offset < 0) return fail(SAR_ERR_SHAPE, "rows, h must be positive and row_offset non-negative");
+  if (c->dtype != SAR_F32 && c->dtype != SAR_BF16) return fail(SAR_ERR_UNSUPPORTED, "dtype %d", c->dtype);
+  if (c->h % 8 != 0) return fail(SAR_ERR_UNSUPPORTED, "h (%lld) must be a multiple of 8", (long long)c->h);
+  if (c->h > 32768) return fail(SAR_ERR_UNSUPPORTED, "h (%lld) above 32768", (long long)c->h);
+  if (c->rows > 0x7fffffffLL) return fail(SAR_ERR_UNSUPPORTED, "rows above 2^31-1");
+  if (!(c->p >= 0.f && c->p < 1.f)) return fail(SAR_ERR_PROB, "dropout probability %g outside [0, 1)", (double)c->p);
+  if (!(c->eps >= 0.f) || !std::isfinite(c->eps)) return fail(SAR_ERR_SHAPE, "eps must be finite and non-negative");
+  if (P) {
+    P->rows = c->rows; P->h = c->h; P->row_offset = c->row_offset;
+    P->eps = c->eps; P->p = c->p; P->keep_scale = 1.0f / (1.0f - c->p);
+    P->thresh = dropout_threshold(c->p);
+    P->key0 = (uint32_t)(c->seed & 0xFFFFFFFFu); P->key1 = (uint32_t)(c->seed >> 32);
+    P->offset = c->offset;
+  }
+  return SAR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sar_last_error(void) { return g_err; }
+
+sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse, void* stream) {
+  sar::AttnParams P;
+  sar_status st = check_attn_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!q || !k || !v || !o || !lse) return fail(SAR_ERR_NULL, "attn_core_fwd: NULL tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return fail(SAR_ERR_ALIGN, "attn_core_fwd: pointer not 16-byte aligned");
+  hipError_t e;
+  if (use_mfma(desc, P)) {
+    e = sar::launch_attn_fwd_mfma(P, q, k, v, o, lse, (hipStream_t)stream);
+  } else {
+    if ((st = check_simple_limits(P)) != SAR_OK) return st;
+    e = sar::launch_attn_fwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, lse, nullptr, nullptr, nullptr, (hipStream_t)stream);
+  }
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_fwd launch");
+}
+
+size_t attn_core_bwd_workspace(const sar_attn_desc* desc) {
+  sar::AttnParams P;
+  if (check_attn_desc(desc, &P) != SAR_OK) return 0;
+  return ((size_t)P.b * P.A * P.s * sizeof(float) + 255) / 256 * 256;  // delta_i = dO_i . O_i per row
+}
+
+static sar_status bwd_recompute_impl(const char* who, const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
+                                     const float* lse, const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                                     int passes, void* stream) {
+  sar::AttnParams P;
+  sar_status st = check_attn_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  const bool rowp = passes & 1, colp = passes & 2;
+  if (!q || !k || !v || !lse || !d_o || (rowp && (!o || !dq)) || (colp && (!dk || !dv))) return fail(SAR_ERR_NULL, "%s: NULL tensor pointer", who);
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) ||
+      !aligned16(dv))
+    return fail(SAR_ERR_ALIGN, "%s: pointer not 16-byte aligned", who);
+  const void* ins[5] = {q, k, v, o, d_o};
+  void* outs[3] = {rowp ? dq : nullptr, colp ? dk : nullptr, colp ? dv : nullptr};
+  for (int x = 0; x < 3; ++x) {
+    if (!outs[x]) continue;
+    for (int y = 0; y < 5; ++y)
+      if (outs[x] == ins[y]) return fail(SAR_ERR_SHAPE, "%s: outputs may not alias inputs", who);
+    for (int y = x + 1; y < 3; ++y)
+      if (outs[x] == outs[y]) return fail(SAR_ERR_SHAPE, "%s: outputs may not alias each other", who);
+  }
+  const size_t need = attn_core_bwd_workspace(desc);
+  if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
+  if (!aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
+  hipError_t e;
+  if (use_mfma(desc, P)) {
+    e = sar::launch_attn_bwd_mfma(P, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace, passes, (hipStream_t)stream);
+  } else {
+    if ((st = check_simple_limits(P)) != SAR_OK) return st;
+    e = sar::launch_attn_bwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace, nullptr, nullptr, nullptr, passes,
+                                    (hipStream_t)stream);
+  }
+  return e == hipSuccess ? SAR_OK : hip_fail(e, who);
+}
+
+sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_recompute_impl("attn_core_bwd_recompute", desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes, 3, stream);
+}
+
+sar_status attn_core_bwd_recompute_dq(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                      const void* d_o, void* dq, void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_recompute_impl("attn_core_bwd_recompute_dq", desc, q, k, v, o, lse, d_o, dq, nullptr, nullptr, workspace, workspace_bytes, 1, stream);
+}
+
+sar_status attn_core_bwd_recompute_dkdv(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const float* lse, const void* d_o,
+                                        void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
+  return bwd_recompute_impl("attn_core_bwd_recompute_dkdv", desc, q, k, v, nullptr, lse, d_o, nullptr, dk, dv, workspace, workspace_bytes, 2, stream);
+}
+
+sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, void* o, void* Pst, uint8_t* Mst, void* Dst,
+                                void* stream) {
+  sar::AttnParams P;
+  sar_status st = check_attn_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!q || !k || !v || !o || !Pst || !Mst || !Dst) return fail(SAR_ERR_NULL, "attn_core_fwd_stored: NULL tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst))
+    return fail(SAR_ERR_ALIGN, "attn_core_fwd_stored: pointer not 16-byte aligned");
+  if ((st = check_simple_limits(P)) != SAR_OK) return st;
+  hipError_t e = sar::launch_attn_fwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, nullptr, Pst, Mst, Dst, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_fwd_stored launch");
+}
+
+sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* Pst, const uint8_t* Mst,
+                                const void* Dst, const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  sar::AttnParams P;
+  sar_status st = check_attn_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!q || !k || !v || !Pst || !Mst || !Dst || !d_o || !dq || !dk || !dv) return fail(SAR_ERR_NULL, "attn_core_bwd_stored: NULL tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst) || !aligned16(d_o) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv))
+    return fail(SAR_ERR_ALIGN, "attn_core_bwd_stored: pointer not 16-byte aligned");
+  const size_t need = attn_core_bwd_workspace(desc);
+  if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
+  if ((st = check_simple_limits(P)) != SAR_OK) return st;
+  hipError_t e = sar::launch_attn_bwd_simple(P, desc->dtype == SAR_BF16, q, k, v, nullptr, nullptr, d_o, dq, dk, dv, (float*)workspace, Pst, Mst, Dst, 3,
+                                             (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_bwd_stored launch");
+}
+
+uint64_t attn_core_saved_bytes(const sar_attn_desc* desc, int selective) {
+  sar::AttnParams P;
+  if (check_attn_desc(desc, &P) != SAR_OK) return 0;
+  const uint64_t esz = desc->dtype == SAR_BF16 ? 2 : 4;
+  const uint64_t qkvo = 4ull * esz * (uint64_t)P.s * P.b * P.A * P.d;       // Q, K, V (6sbh/t) + O (2sbh/t)
+  if (selective) return qkvo;                                               // Section 5: no s^2 term
+  return qkvo + (2ull * esz + 1ull) * (uint64_t)P.A * P.s * P.s * P.b;      // + softmax out, mask, dropout out
+}
+
+uint64_t attn_core_small_buffer_bytes(const sar_attn_desc* desc) {
+  sar::AttnParams P;
+  if (check_attn_desc(desc, &P) != SAR_OK) return 0;
+  return 4ull * (uint64_t)P.A * P.s * P.b + 16ull;
+}
+
+uint64_t attn_core_philox_count(const sar_attn_desc* desc) {
+  if (check_attn_desc(desc, nullptr) != SAR_OK) return 0;
+  return (uint64_t)desc->b * (uint64_t)desc->a * (uint64_t)desc->s * (uint64_t)desc->s / 8ull;
+}
+
+sar_status ln_fwd(const sar_rows_desc* desc, const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!x || !gamma || !beta || !y || !mean || !rstd) return fail(SAR_ERR_NULL, "ln_fwd: NULL tensor pointer");
+  if (!aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(y)) return fail(SAR_ERR_ALIGN, "ln_fwd: pointer not 16-byte aligned");
+  hipError_t e = sar::launch_ln_fwd(P, desc->dtype == SAR_BF16, x, gamma, beta, y, mean, rstd, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "ln_fwd launch");
+}
+
+size_t ln_bwd_workspace(const sar_rows_desc* desc) {
+  if (check_rows_desc(desc, nullptr) != SAR_OK) return 0;
+  return sar::ln_bwd_workspace_bytes(desc->rows, desc->h);
+}
+
+sar_status ln_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
+                  float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!dy || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta) return fail(SAR_ERR_NULL, "ln_bwd: NULL tensor pointer");
+  if (!aligned16(dy) || !aligned16(x) || !aligned16(gamma) || !aligned16(dx)) return fail(SAR_ERR_ALIGN, "ln_bwd: pointer not 16-byte aligned");
+  const size_t need = sar::ln_bwd_workspace_bytes(P.rows, P.h);
+  if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
+  if (!aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
+  hipError_t e = sar::launch_ln_bwd(P, desc->dtype == SAR_BF16, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "ln_bwd launch");
+}
+
+sar_status bias_dropout_add(const sar_rows_desc* desc, const void* x, const void* bias, const void* resid, void* out, uint8_t* mask_out, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!x || !resid || !out) return fail(SAR_ERR_NULL, "bias_dropout_add: NULL tensor pointer");
+  if (!aligned16(x) || !aligned16(resid) || !aligned16(out) || (bias && !aligned16(bias)) || (mask_out && (reinterpret_cast<uintptr_t>(mask_out) & 7u)))
+    return fail(SAR_ERR_ALIGN, "bias_dropout_add: pointer not aligned (16 bytes; mask 8 bytes)");
+  if (out == x) return fail(SAR_ERR_SHAPE, "bias_dropout_add: out may alias resid only");
+  hipError_t e = sar::launch_bias_dropout_add(P, desc->dtype == SAR_BF16, x, bias, resid, out, mask_out, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_dropout_add launch");
+}
+
+}  // extern "C"

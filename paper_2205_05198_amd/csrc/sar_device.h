@@ -1,0 +1,93 @@
+// Device-side helpers shared by the HIP kernels of libsar (gfx950 only): bf16 conversion, Philox4x32-10,
+// wavefront reductions.  Nothing here is used by, or shared with, the CPU oracle.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sar {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;   // MFMA A/B operand (8 bf16)
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4_t;     // ds_read_b64_tr_b16 result
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float float16_t;   // 32x32 MFMA accumulator
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float float4_t;
+
+// ---- bf16 <-> fp32 (round to nearest even), on raw 16-bit patterns ----
+__device__ __forceinline__ float bf16_to_f32(uint16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+// two floats -> packed bf16 pair (lo = a, hi = b)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+  typedef __attribute__((__vector_size__(2 * sizeof(float)))) float float2_t;
+  float2_t f = {a, b};
+  bf16x2_t r = __builtin_convertvector(f, bf16x2_t);  // v_cvt_pk_bf16_f32, RNE
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// element load/store abstraction for the generic (non-MFMA) kernels
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {  // bf16 bit pattern
+  static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// ---- Philox4x32-10 (Salmon et al., SC'11); the four output words for counter (g_lo, g_hi, 0, site) ----
+struct Philox4 { uint32_t x, y, z, w; };
+__device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c1 = (uint32_t)p1;
+    c3 = (uint32_t)p0;
+    c0 = n0;
+    c2 = n2;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  Philox4 o = {c0, c1, c2, c3};
+  return o;
+}
+// the eight 16-bit fields of one call, for elements 8G .. 8G+7, as keep bits (bit r set = element r kept)
+__device__ __forceinline__ uint32_t keep_bits8(uint64_t G, uint32_t site, uint32_t k0, uint32_t k1, uint32_t T) {
+  Philox4 o = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), 0u, site, k0, k1);
+  uint32_t m = 0;
+  m |= ((o.x & 0xFFFFu) >= T) ? 1u : 0u;
+  m |= ((o.x >> 16) >= T) ? 2u : 0u;
+  m |= ((o.y & 0xFFFFu) >= T) ? 4u : 0u;
+  m |= ((o.y >> 16) >= T) ? 8u : 0u;
+  m |= ((o.z & 0xFFFFu) >= T) ? 16u : 0u;
+  m |= ((o.z >> 16) >= T) ? 32u : 0u;
+  m |= ((o.w & 0xFFFFu) >= T) ? 64u : 0u;
+  m |= ((o.w >> 16) >= T) ? 128u : 0u;
+  return m;
+}
+// keep bit of a single element e
+__device__ __forceinline__ uint32_t keep_bit1(uint64_t e, uint64_t offset, uint32_t site, uint32_t k0, uint32_t k1, uint32_t T) {
+  uint32_t m = keep_bits8(offset + (e >> 3), site, k0, k1, T);
+  return (m >> (uint32_t)(e & 7u)) & 1u;
+}
+
+// ---- wavefront (64 lanes) reductions ----
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+}  // namespace sar

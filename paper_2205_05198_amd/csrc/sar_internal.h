@@ -1,0 +1,53 @@
+// Host-side declarations shared by the translation units of libsar: kernel parameter blocks and the
+// launchers each .hip file exports to the C-ABI layer (sar_api.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sar {
+
+struct AttnParams {
+  int s, b, A, d;               // per-GPU share: A = a/t local heads, d = h/a
+  int a_global, head0;          // global head count and global index of local head 0 (Philox indexing)
+  int64_t stride_s, stride_b, stride_a;
+  float scale;                  // alpha
+  float p, keep_scale;          // dropout probability and 1/(1-p) in fp32
+  uint32_t thresh;              // keep iff 16-bit field >= thresh
+  uint32_t key0, key1;          // Philox key = seed
+  uint64_t offset;              // Philox counter base
+};
+
+struct RowsParams {
+  int64_t rows, h, row_offset;
+  float eps, p, keep_scale;
+  uint32_t thresh, key0, key1;
+  uint64_t offset;
+};
+
+// attn_simple.hip: one-wave-per-row kernels in plain fp32 arithmetic, any d % 4 == 0 up to 256; also the
+// stored-activation baseline (P, M, D written / read).
+hipError_t launch_attn_fwd_simple(const AttnParams& P, bool bf16, const void* q, const void* k, const void* v, void* o, float* lse,
+                                  void* Pst, uint8_t* Mst, void* Dst, hipStream_t st);
+// passes: bit 0 = row pass (dq, writes delta), bit 1 = column pass (dk, dv, reads delta)
+hipError_t launch_attn_bwd_simple(const AttnParams& P, bool bf16, const void* q, const void* k, const void* v, const void* o,
+                                  const float* lse, const void* dO, void* dq, void* dk, void* dv, float* delta,
+                                  const void* Pst, const uint8_t* Mst, const void* Dst, int passes, hipStream_t st);
+size_t attn_simple_lds_bytes(int s);
+
+// attn_mfma.hip: bf16 MFMA kernels, d in {64, 96, 128, 160}
+bool attn_mfma_supported(int d);
+hipError_t launch_attn_fwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, void* o, float* lse, hipStream_t st);
+hipError_t launch_attn_bwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                const void* dO, void* dq, void* dk, void* dv, float* delta, int passes, hipStream_t st);
+
+// rows.hip: LayerNorm forward/backward and bias-dropout-add on [rows, h]
+hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                         float* rstd, hipStream_t st);
+size_t ln_bwd_workspace_bytes(int64_t rows, int64_t h);
+hipError_t launch_ln_bwd(const RowsParams& P, bool bf16, const void* dy, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, void* dx, float* dgamma, float* dbeta, void* ws, hipStream_t st);
+hipError_t launch_bias_dropout_add(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, void* out,
+                                   uint8_t* mask, hipStream_t st);
+
+}  // namespace sar
