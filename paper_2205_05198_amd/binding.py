@@ -13,8 +13,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB_PATH = os.path.join(_HERE, "libsar.so")
 _SOURCES = ["sar_api.hip", "attn_simple.hip", "attn_mfma.hip", "rows.hip"]
+# -amdgpu-mfma-vgpr-form: keep matrix-core accumulators in the VGPR file; with the default heuristics the
+# compiler parks them in AGPRs and copies all of them through VGPRs on every trip of the tile loops.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 SAR_F32, SAR_BF16 = 0, 1
 

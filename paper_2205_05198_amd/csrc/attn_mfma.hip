@@ -33,7 +33,19 @@ static constexpr float kLn2 = 0.6931471805599453f;
 typedef __attribute__((address_space(3))) short4_t lds_short4_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 
+#ifdef SAR_EXP_NOMFMA
+__device__ __forceinline__ float16_t mfma32(bf16x8_t a, bf16x8_t b, float16_t c) { c[0] += (float)a[0] + (float)b[0]; return c; }
+#else
 __device__ __forceinline__ float16_t mfma32(bf16x8_t a, bf16x8_t b, float16_t c) { return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0); }
+#endif
+#ifdef SAR_EXP_NOEXP
+#define SAR_EXP2(x) ((x) * 0.001f)
+#else
+#define SAR_EXP2(x) __builtin_amdgcn_exp2f(x)
+#endif
+#ifdef SAR_EXP_NOPHILOX
+#define keep_bits8(G, site, k0, k1, T) ((uint32_t)(G) | 0xFFu)
+#endif
 
 // 16-byte operand from LDS / global (8 consecutive bf16)
 __device__ __forceinline__ bf16x8_t ld_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
@@ -87,6 +99,9 @@ struct TileBuf { u32x4_t r[TileMap<D>::ITER]; };
 // gtile points at the tile's first row (uniform); rows_valid = rows of the tensor left from there (clamped reads)
 template <int D>
 __device__ __forceinline__ void tile_fetch(TileBuf<D>& buf, const TileMap<D>& map, const uint16_t* gtile, int gstride, int rows_valid, int tid) {
+#ifdef SAR_EXP_NOFETCH
+  if (rows_valid > -1000000) return;
+#endif
   if (rows_valid >= TileMap<D>::ROWS) {
 #pragma unroll
     for (int it = 0; it < TileMap<D>::ITER; ++it) buf.r[it] = *reinterpret_cast<const u32x4_t*>(gtile + map.goff[it]);
@@ -144,7 +159,7 @@ __device__ __forceinline__ void store_acc_row(uint16_t* row, const float16_t (&a
     }
 }
 
-static constexpr float kLazyRescale = 8.0f;  // the running reference exponent moves only when the row maximum grew by > 2^8
+static constexpr float kLazyRescale = 60.0f;  // the running reference exponent moves only when the row maximum grew by > 2^60
 
 // ===================================================================================================
 // Forward.  Workgroup = 64 query rows: wave = (rg, ks), rg = 32-row group, ks = which 32 keys of each 64-key
@@ -223,7 +238,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
         mt = fmaxf(mt, x);
       }
       mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-      if (__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale)) {
+      if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale) != 0, 0)) {
         const float m_new = fmaxf(m_ref, mt);
         const float corr = __builtin_amdgcn_exp2f(m_ref - m_new);
         m_ref = m_new;
@@ -241,7 +256,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
         float pd[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float pe = __builtin_amdgcn_exp2f(st[8 * c + e] - m_ref);
+          const float pe = SAR_EXP2(st[8 * c + e] - m_ref);
           psum += pe;
           pd[e] = ((keep >> e) & 1u) ? pe : 0.f;
         }
@@ -372,8 +387,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
         float ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          if (diag && (jc + e > i)) pe = 0.f;
+          const float pex = SAR_EXP2(fmaf(st[8 * c + e], sc2, -lse2));
+          const float pe = (diag && (jc + e > i)) ? 0.f : pex;
           const float dp = ((keep >> e) & 1u) ? dd[8 * c + e] * P.keep_scale : 0.f;
           ds[e] = pe * (dp - dl);
         }
@@ -518,8 +533,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         float dvv[8], ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          if (!row_ok || (diag && (jc + e > i))) pe = 0.f;
+          const float pex = SAR_EXP2(fmaf(st[8 * c + e], sc2, -lse2));
+          const bool dead = !row_ok || (diag && (jc + e > i));
+          const float pe = dead ? 0.f : pex;
           const float km = ((keep >> e) & 1u) ? P.keep_scale : 0.f;
           dvv[e] = pe * km;
           ds[e] = pe * (dd[8 * c + e] * km - dl);
