@@ -12,11 +12,17 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB_PATH = os.path.join(_HERE, "libsar.so")
-_SOURCES = ["sar_api.hip", "attn_simple.hip", "attn_mfma.hip", "rows.hip"]
-# -amdgpu-mfma-vgpr-form: keep matrix-core accumulators in the VGPR file; with the default heuristics the
-# compiler parks them in AGPRs and copies all of them through VGPRs on every trip of the tile loops.
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form"]
+# source file -> extra hipcc flags.  -amdgpu-mfma-vgpr-form keeps matrix-core accumulators in the VGPR file: with the
+# default heuristics the compiler parks them in AGPRs and copies all of them through VGPRs on every trip of the tile
+# loops.  The dK/dV pass needs both register files (2 accumulator sets) and pins its accumulators to AGPRs itself.
+_SOURCES = {
+    "sar_api.hip": [],
+    "attn_simple.hip": [],
+    "attn_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "attn_mfma_cols.hip": [],
+    "rows.hip": [],
+}
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 SAR_F32, SAR_BF16 = 0, 1
 
@@ -64,13 +70,26 @@ def library_path() -> str:
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source of the package for gfx950 into libsar.so (hipcc cross-compiles without a GPU)."""
-    cmd = ["hipcc", *HIPCC_FLAGS, *[os.path.join(_CSRC, f) for f in _SOURCES], "-o", _LIB_PATH]
+    """Compile every HIP source of the package for gfx950 and link libsar.so (hipcc cross-compiles without a GPU)."""
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = []
+    procs = []
+    for src, extra in _SOURCES.items():
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        cmd = ["hipcc", *HIPCC_FLAGS, *extra, "-c", os.path.join(_CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd))
+        procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    for cmd, pr in procs:
+        out, _ = pr.communicate()
+        if pr.returncode != 0:
+            raise RuntimeError("hipcc failed: " + " ".join(cmd) + "\n" + out)
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", _LIB_PATH]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    if verbose:
-        print(" ".join(cmd))
+        raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
     return _LIB_PATH
 
 

@@ -1,0 +1,211 @@
+// bf16 attention core, backward column pass (dK, dV) on gfx950 matrix cores.  See attn_mfma_rows.hip for the tile
+// layouts shared by the three kernels.  This file is compiled WITHOUT -amdgpu-mfma-vgpr-form: its two accumulator
+// sets (2 x head_dim/32 x 16 registers) live in AGPRs so that the 256 VGPRs stay free for operands.
+#include "attn_mfma_common.h"
+
+namespace sar {
+
+// ===================================================================================================
+// Backward, column-stationary pass.  Workgroup = 64 keys: wave = (kgp, is), kgp = 32-key group whose dK, dV
+// accumulators it keeps in registers, is = which 32 query rows of each 64-row tile it sweeps.
+//   dV_j = sum_i D_ij dO_i,  dK_j = alpha sum_i dS_ij q_i.
+// P, D, dS are produced with one query row per lane; the two products above contract over i, so the bf16
+// tiles are first moved to the one-key-per-lane layout by multiplying with an identity on the matrix core.
+// ===================================================================================================
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                                const uint16_t* __restrict__ v, const float* __restrict__ lse,
+                                                                const uint16_t* __restrict__ dO, const float* __restrict__ delta,
+                                                                uint16_t* __restrict__ dk, uint16_t* __restrict__ dv) {
+  constexpr int BN = 64, BI = 64, KP = D + 8, KC = D / 16, DT = D / 32;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * 64 * KP];
+  __shared__ float lse_s[BI], delta_s[BI];
+  uint16_t* Ksm = smem;                 // this workgroup's keys, rows swapped inside groups of 32
+  uint16_t* Vsm = smem + 64 * KP;
+  uint16_t* Qs = smem + 2 * 64 * KP;    // current 64 query rows, natural order
+  uint16_t* dOs = smem + 3 * 64 * KP;
+
+  const int N = P.b * P.A;
+  const int kb = (int)(blockIdx.x / N);  // key block 0 sweeps the most rows: heaviest first
+  const int bn = blockIdx.x % N, beta = bn / P.A, n = bn % P.A;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const int kgp = wave & 1, is = wave >> 1;
+  const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
+  const int gstride = (int)P.stride_s;
+  const int jw0 = kb * BN + kgp * 32;  // first key of this wave
+
+  TileMap<D> map;
+  map.init(tid, gstride, KP, true);
+  {
+    TileBuf<D> kbuf, vbuf;
+    tile_fetch(kbuf, map, k + base + (int64_t)(kb * BN) * gstride, gstride, P.s - kb * BN, tid);
+    tile_fetch(vbuf, map, v + base + (int64_t)(kb * BN) * gstride, gstride, P.s - kb * BN, tid);
+    tile_commit(kbuf, map, Ksm);
+    tile_commit(vbuf, map, Vsm);
+  }
+  map.init(tid, gstride, KP, false);
+  // A operands of S^T and dD^T: LDS row 32*kgp + li holds key jw0 + perm_row(li)
+  const uint16_t* kw = Ksm + (32 * kgp + li) * KP + 8 * hh;
+  const uint16_t* vw = Vsm + (32 * kgp + li) * KP + 8 * hh;
+  // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
+  bf16x8_t ident[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    union { uint16_t h[8]; bf16x8_t v; } u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) u.h[e] = (li == 16 * c + 8 * hh + e) ? (uint16_t)0x3F80 : (uint16_t)0;
+    ident[c] = u.v;
+  }
+  float16_t dkacc[DT], dvacc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
+
+  const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
+  const float sc2 = P.scale * kLog2e;
+  const int nit = (P.s + BI - 1) / BI;
+  const int it0 = kb;  // BI == BN: the first tile with rows >= this block's keys
+  const uint16_t* qg = q + base;
+  const uint16_t* dog = dO + base;
+  TileBuf<D> qbuf, dobuf;
+  float lse_n = 0.f, delta_n = 0.f;
+  tile_fetch(qbuf, map, qg + (int64_t)(it0 * BI) * gstride, gstride, P.s - it0 * BI, tid);
+  tile_fetch(dobuf, map, dog + (int64_t)(it0 * BI) * gstride, gstride, P.s - it0 * BI, tid);
+  if (tid < BI) {
+    const int ir = min(it0 * BI + tid, P.s - 1);
+    lse_n = lse[(size_t)bn * P.s + ir];
+    delta_n = delta[(size_t)bn * P.s + ir];
+  }
+  for (int it = it0; it < nit; ++it) {
+    const int i0 = it * BI;
+    __syncthreads();
+    tile_commit(qbuf, map, Qs);
+    tile_commit(dobuf, map, dOs);
+    if (tid < BI) {
+      lse_s[tid] = lse_n * kLog2e;
+      delta_s[tid] = delta_n;
+    }
+    __syncthreads();
+    if (it + 1 < nit) {  // next tile's global loads fly while this one is computed
+      tile_fetch(qbuf, map, qg + (int64_t)(i0 + BI) * gstride, gstride, P.s - (i0 + BI), tid);
+      tile_fetch(dobuf, map, dog + (int64_t)(i0 + BI) * gstride, gstride, P.s - (i0 + BI), tid);
+      if (tid < BI) {
+        const int ir = min(i0 + BI + tid, P.s - 1);
+        lse_n = lse[(size_t)bn * P.s + ir];
+        delta_n = delta[(size_t)bn * P.s + ir];
+      }
+    }
+    const int i0w = i0 + 32 * is;  // this wave's 32 rows
+    if (i0w + 31 >= jw0) {         // otherwise every row precedes this wave's keys
+      const bool diag = (i0w < jw0 + 31);
+      float16_t st, dd;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        st = mfma32(ld_frag(kw + 16 * kc), ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
+        dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
+      }
+      const int i = i0w + li;
+      const float lse2 = lse_s[32 * is + li], dl = delta_s[32 * is + li];
+      const uint64_t rowG = headG + (uint64_t)min(i, P.s - 1) * (uint64_t)(P.s >> 3);
+      const bool row_ok = i < P.s;
+      bf16x8_t df[2], dsf[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const int jc = jw0 + 16 * c + 8 * hh;
+        const uint32_t keep = keep_bits8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1, P.thresh);
+        float dvv[8], ds[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float pex = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
+          const bool dead = !row_ok || (diag && (jc + e > i));
+          const float pe = dead ? 0.f : pex;
+          const float km = ((keep >> e) & 1u) ? P.keep_scale : 0.f;
+          dvv[e] = pe * km;
+          ds[e] = pe * (dd[8 * c + e] * km - dl);
+        }
+        df[c] = pack8(dvv);
+        dsf[c] = pack8(ds);
+      }
+      // one-key-per-lane copies: T[i][key] = sum_k tile[i][k] I[k][key]
+      float16_t tD, tS;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { tD[e] = 0.f; tS[e] = 0.f; }
+      tD = mfma32(df[0], ident[0], tD);
+      tS = mfma32(dsf[0], ident[0], tS);
+      tD = mfma32(df[1], ident[1], tD);
+      tS = mfma32(dsf[1], ident[1], tS);
+      // acc[4g + r] <-> row 8g + 4hh + r: operand X takes g in {2X, 2X+1}, i.e. rows 16X + 8*(e>>2) + 4hh + (e&3)
+#pragma unroll
+      for (int X = 0; X < 2; ++X) {
+        float td[8], ts[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { td[e] = tD[8 * X + e]; ts[e] = tS[8 * X + e]; }
+        const bf16x8_t dT = pack8(td), sT = pack8(ts);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          dvacc[dt] = mfma32(ld_frag_tr_perm(dOs, KP, 32 * is + 16 * X, 32 * dt, lane), dT, dvacc[dt]);
+          dkacc[dt] = mfma32(ld_frag_tr_perm(Qs, KP, 32 * is + 16 * X, 32 * dt, lane), sT, dkacc[dt]);
+        }
+      }
+    }
+    // Keep the loop-carried accumulators in the accumulation registers (AGPRs) across the back-edge; without
+    // this the compiler copies all of them to VGPRs and back on every trip.
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      asm volatile("" : "+a"(dkacc[dt]));
+      asm volatile("" : "+a"(dvacc[dt]));
+    }
+  }
+  // ---- sum the two row halves, scale, store ----
+  __syncthreads();
+  float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
+  if (is == 1) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        mg[(32 * dt + e) * 64 + lane] = dkacc[dt][e];
+        mg[(32 * dt + 16 + e) * 64 + lane] = dvacc[dt][e];
+      }
+  }
+  __syncthreads();
+  if (is == 0) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        dkacc[dt][e] += mg[(32 * dt + e) * 64 + lane];
+        dvacc[dt][e] += mg[(32 * dt + 16 + e) * 64 + lane];
+      }
+    const int key = jw0 + li;
+    if (key < P.s) {
+      store_acc_row<DT>(dk + base + (int64_t)key * P.stride_s, dkacc, P.scale, hh);
+      store_acc_row<DT>(dv + base + (int64_t)key * P.stride_s, dvacc, 1.0f, hh);
+    }
+  }
+}
+
+template <int D>
+static hipError_t bwd_dkdv_d(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO, const float* delta,
+                             void* dk, void* dv, hipStream_t st) {
+  const int N = P.b * P.A, nb = (P.s + 63) / 64;
+  hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                     (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
+                                     const float* delta, void* dk, void* dv, hipStream_t st) {
+  switch (P.d) {
+    case 64: return bwd_dkdv_d<64>(P, q, k, v, lse, dO, delta, dk, dv, st);
+    case 96: return bwd_dkdv_d<96>(P, q, k, v, lse, dO, delta, dk, dv, st);
+    case 128: return bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, st);
+    case 160: return bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace sar

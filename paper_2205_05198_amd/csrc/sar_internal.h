@@ -35,11 +35,14 @@ hipError_t launch_attn_bwd_simple(const AttnParams& P, bool bf16, const void* q,
                                   const void* Pst, const uint8_t* Mst, const void* Dst, int passes, hipStream_t st);
 size_t attn_simple_lds_bytes(int s);
 
-// attn_mfma.hip: bf16 MFMA kernels, d in {64, 96, 128, 160}
+// attn_mfma_rows.hip (forward, dQ pass) and attn_mfma_cols.hip (dK/dV pass): bf16 MFMA kernels, d in {64, 96, 128, 160}
 bool attn_mfma_supported(int d);
 hipError_t launch_attn_fwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, void* o, float* lse, hipStream_t st);
 hipError_t launch_attn_bwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                 const void* dO, void* dq, void* dk, void* dv, float* delta, int passes, hipStream_t st);
+
+hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
+                                     const float* delta, void* dk, void* dv, hipStream_t st);
 
 // rows.hip: LayerNorm forward/backward and bias-dropout-add on [rows, h]
 hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* gamma, const void* beta, void* y, float* mean,
