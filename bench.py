@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--workload", default="530B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stored-steps", type=int, default=2, help="steps of the stored-activation baseline (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (known traffic) so that FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -88,6 +90,13 @@ def main():
         mark(5)
         sar.bias_dropout_add(rdesc, x, bias, resid, out, None)
         mark(6)
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -264,7 +264,7 @@ hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const vo
 
 static inline void ln_bwd_plan(int64_t rows, int64_t h, int& nslab, int& nsplit, int& rows_per_split) {
   nslab = (int)((h + 63) / 64);
-  int want = (1024 + nslab - 1) / nslab;                 // aim at >= 1024 workgroups
+  int want = (256 + nslab - 1) / nslab;                  // aim at >= 256 workgroups (one per CU)
   int maxsplit = (int)((rows + 31) / 32);                 // at least one 32-row step per split
   nsplit = want < 1 ? 1 : (want > maxsplit ? maxsplit : want);
   if (nsplit < 1) nsplit = 1;
@@ -299,6 +299,11 @@ static hipError_t ln_bwd_t(const RowsParams& P, const void* dy, const void* x, c
 #undef SAR_LN_RS
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (nsplit == 1) {  // one workgroup per column slab sees every row: it writes dgamma / dbeta itself
+    hipLaunchKernelGGL((ln_bwd_slab_kernel<T>), dim3(nslab, 1), dim3(256), 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma,
+                       (const float2*)rowstat, (T*)dx, dgamma, dbeta, rps);
+    return hipGetLastError();
+  }
   // partial layout [split][2][h]: dgamma part at +0, dbeta part at +h
   hipLaunchKernelGGL((ln_bwd_slab_kernel<T>), dim3(nslab, nsplit), dim3(256), 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma,
                      (const float2*)rowstat, (T*)dx, part, part + P.h, rps);
