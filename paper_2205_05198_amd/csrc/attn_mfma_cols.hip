@@ -110,7 +110,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
       const int i = i0w + li;
       const float lse2 = lse_s[32 * is + li], dl = delta_s[32 * is + li];
       const uint64_t rowG = headG + (uint64_t)min(i, P.s - 1) * (uint64_t)(P.s >> 3);
-      const bool row_ok = i < P.s;
+      if (diag || i0w + 31 >= P.s) {  // uniform per wave: keys j > i and rows past the end get probability exp2(-inf) = 0
+        asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (i >= P.s || jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+      }
       bf16x8_t df[2], dsf[2];
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
@@ -119,9 +124,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         float dvv[8], ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float pex = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          const bool dead = !row_ok || (diag && (jc + e > i));
-          const float pe = dead ? 0.f : pex;
+          const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
           const float km = ((keep >> e) & 1u) ? P.keep_scale : 0.f;
           dvv[e] = pe * km;
           ds[e] = pe * (dd[8 * c + e] * km - dl);

@@ -50,13 +50,13 @@ template <int D>
 struct TileMap {
   static constexpr int ROWS = 64, NT = 256, CPR = D / 8, NCH = ROWS * CPR, ITER = NCH / NT;
   static_assert(NCH % NT == 0, "tile must split evenly over 256 threads");
-  int goff[ITER];  // element offset of the chunk from the tile's first row in global memory
+  uint32_t goff[ITER];  // BYTE offset of the chunk from the tile's first row in global memory (uniform base + 32-bit lane offset addressing)
   int loff[ITER];  // element offset of the chunk inside the LDS tile
   __device__ __forceinline__ void init(int tid, int gstride, int pitch, bool perm) {
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
       const int c = tid + it * NT, r = c / CPR, cc = c - r * CPR;
-      goff[it] = r * gstride + 8 * cc;
+      goff[it] = 2u * (uint32_t)(r * gstride + 8 * cc);
       loff[it] = (perm ? perm_row(r) : r) * pitch + 8 * cc;
     }
   }
@@ -69,7 +69,7 @@ template <int D>
 __device__ __forceinline__ void tile_fetch(TileBuf<D>& buf, const TileMap<D>& map, const uint16_t* gtile, int gstride, int rows_valid, int tid) {
   if (rows_valid >= TileMap<D>::ROWS) {
 #pragma unroll
-    for (int it = 0; it < TileMap<D>::ITER; ++it) buf.r[it] = *reinterpret_cast<const u32x4_t*>(gtile + map.goff[it]);
+    for (int it = 0; it < TileMap<D>::ITER; ++it) buf.r[it] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const char*>(gtile) + map.goff[it]);
   } else {
 #pragma unroll
     for (int it = 0; it < TileMap<D>::ITER; ++it) {
@@ -83,6 +83,54 @@ template <int D>
 __device__ __forceinline__ void tile_commit(const TileBuf<D>& buf, const TileMap<D>& map, uint16_t* lds) {
 #pragma unroll
   for (int it = 0; it < TileMap<D>::ITER; ++it) *reinterpret_cast<u32x4_t*>(lds + map.loff[it]) = buf.r[it];
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Direct global -> LDS tile loads (global_load_lds_dwordx4): lane L of a wave-wide load writes its 16 bytes
+// at (wave-uniform LDS base) + 16 L, without passing through registers.  A tile of 64 rows whose LDS pitch
+// is D + 8 elements = CPR + 1 chunks of 16 bytes (the last chunk of a row is padding) is exactly CPR + 1
+// such loads of 64 consecutive chunks; wave w of the workgroup issues loads w, w + 4, ...  Lanes that fall
+// on a padding chunk re-read the row's last chunk.  Several tiles with the same row stride (K and V, or Q and
+// dO) share one offset table.  Completion: vmcnt of the issuing wave, then a workgroup barrier.
+// ---------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void_t;
+typedef __attribute__((address_space(1))) const void glb_void_t;
+
+template <int D>
+struct DmaMap {
+  static constexpr int ROWS = 64, CPR = D / 8, NL = CPR + 1, PER = (NL + 3) / 4;
+  static constexpr int TILE = ROWS * (D + 8);  // elements of one LDS tile
+  uint32_t goff[PER];                          // byte offset of this lane's chunk from the tile's first row
+  bool perm;
+  // rows_valid: rows of the tensor left from the tile's first row (reads of later rows are clamped to the last one)
+  __device__ __forceinline__ void init(int wave, int lane, int gstride, bool perm_rows, int rows_valid = ROWS) {
+    perm = perm_rows;
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int L = 64 * (wave + 4 * u) + lane, r0 = (L / NL) & (ROWS - 1), c0 = L - (L / NL) * NL;
+      int r = perm_rows ? perm_row(r0) : r0;
+      r = r < rows_valid ? r : rows_valid - 1;
+      goff[u] = 2u * (uint32_t)(r * gstride + 8 * (c0 < CPR ? c0 : CPR - 1));
+    }
+  }
+};
+
+// gtile: first row of the tile in global memory (uniform); lds: the tile's place in LDS (uniform)
+template <int D>
+__device__ __forceinline__ void dma_tile(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave) {
+#pragma unroll
+  for (int u = 0; u < DmaMap<D>::PER; ++u) {
+    const int l = wave + 4 * u;
+    if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)  // only the last round can run past the tile
+      __builtin_amdgcn_global_load_lds((glb_void_t*)(reinterpret_cast<const char*>(gtile) + map.goff[u]), (lds_void_t*)(lds + 512 * l), 16, 0, 0);
+  }
+}
+// the same for a tile that ends before its 64th row: offsets recomputed with clamped rows
+template <int D>
+__device__ __forceinline__ void dma_tile_ragged(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, int lane, int gstride, int rows_valid) {
+  DmaMap<D> m2;
+  m2.init(wave, lane, gstride, map.perm, rows_valid);
+  dma_tile<D>(m2, gtile, lds, wave);
 }
 
 // Same as ld_frag_tr but for the k order that the swapped rows and the identity-transposed tiles use:

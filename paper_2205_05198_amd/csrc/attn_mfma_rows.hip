@@ -30,15 +30,15 @@ static constexpr float kLazyRescale = 60.0f;  // the running reference exponent 
 
 // ===================================================================================================
 // Forward.  Workgroup = 64 query rows: wave = (rg, ks), rg = 32-row group, ks = which 32 keys of each 64-key
-// tile.  K and V tiles are staged in LDS, both with swapped rows.
+// tile.  K and V tiles (both with swapped rows) go from global memory straight into one of two LDS stages;
+// the loads of tile j+1 are issued right after the single barrier of step j and land while tile j is computed.
 // ===================================================================================================
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
   constexpr int BM = 64, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * BN * KP];
-  uint16_t* Ks = smem;
-  uint16_t* Vs = smem + BN * KP;
+  constexpr int TILE = BN * KP;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];  // stage 0: K, V; stage 1: K, V
 
   const int N = P.b * P.A;
   const int nrb = (P.s + BM - 1) / BM;
@@ -69,23 +69,33 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
 
   const int last_row = min(rb * BM + BM - 1, P.s - 1);
   const int ntile = last_row / BN + 1;
-  TileMap<D> map;
-  map.init(tid, gstride, KP, true);
-  TileBuf<D> kbuf, vbuf;
+  DmaMap<D> map;
+  map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
   const uint16_t* vg = v + base;
-  tile_fetch(kbuf, map, kg, gstride, P.s, tid);
-  tile_fetch(vbuf, map, vg, gstride, P.s, tid);
+  if (P.s >= BN) {
+    dma_tile<D>(map, kg, smem, wave);
+    dma_tile<D>(map, vg, smem + TILE, wave);
+  } else {
+    dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
+    dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
+  }
   for (int jt = 0; jt < ntile; ++jt) {
     const int j0 = jt * BN;
-    __syncthreads();  // every wave is done reading the previous tile
-    tile_commit(kbuf, map, Ks);
-    tile_commit(vbuf, map, Vs);
-    __syncthreads();
-    if (jt + 1 < ntile) {  // next tile's global loads fly while this one is computed
-      tile_fetch(kbuf, map, kg + (int64_t)(j0 + BN) * gstride, gstride, P.s - (j0 + BN), tid);
-      tile_fetch(vbuf, map, vg + (int64_t)(j0 + BN) * gstride, gstride, P.s - (j0 + BN), tid);
+    __syncthreads();  // tile jt has landed (every wave waited for its own loads); nobody reads the other stage any more
+    if (jt + 1 < ntile) {
+      uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
+      const int left = P.s - (j0 + BN);
+      if (left >= BN) {
+        dma_tile<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave);
+        dma_tile<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave);
+      } else {
+        dma_tile_ragged<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave, lane, gstride, left);
+        dma_tile_ragged<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave, lane, gstride, left);
+      }
     }
+    const uint16_t* Ks = smem + (jt & 1) * 2 * TILE;
+    const uint16_t* Vs = Ks + TILE;
     const int j0w = j0 + 32 * ks;  // this wave's 32 keys
     if (j0w <= iw0 + 31) {
       // ---- S^T = K Q^T ----
@@ -95,16 +105,18 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) st = mfma32(ld_frag(Ks + (32 * ks + li) * KP + 16 * kc + 8 * hh), qf[kc], st);
       // st[8*c + e] is the score of key j0w + 16*c + 8*hh + e against query row i
-      const bool diag = (j0w + 31 > iw0);
-      float mt = -INFINITY;
+      if (j0w + 31 > iw0) {  // tile touches the diagonal (uniform per wave): mask keys j > i
+        asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float x = st[e] * sc2;
-        if (diag && (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i)) x = -INFINITY;
-        st[e] = x;
-        mt = fmaxf(mt, x);
+        for (int e = 0; e < 16; ++e)
+          if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
       }
-      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      // the softmax runs on alpha*log2(e)*score; alpha > 0, so the maximum can be taken on the raw scores
+      float mt = fmaxf(fmaxf(st[0], st[1]), st[2]);
+#pragma unroll
+      for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, st[e]), st[e + 1]);
+      mt = fmaxf(mt, st[15]);
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2;
       if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale) != 0, 0)) {
         const float m_new = fmaxf(m_ref, mt);
         const float corr = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
         float pd[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float pe = __builtin_amdgcn_exp2f(st[8 * c + e] - m_ref);
+          const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
           psum += pe;
           pd[e] = ((keep >> e) & 1u) ? pe : 0.f;
         }
@@ -179,9 +191,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
                                                               const float* __restrict__ lse, const uint16_t* __restrict__ dO,
                                                               uint16_t* __restrict__ dq, float* __restrict__ delta) {
   constexpr int BM = 64, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * BN * KP];
-  uint16_t* Ks = smem;
-  uint16_t* Vs = smem + BN * KP;
+  constexpr int TILE = BN * KP;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];  // stage 0: K, V; stage 1: K, V
 
   const int N = P.b * P.A;
   const int nrb = (P.s + BM - 1) / BM;
@@ -218,23 +229,33 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
 
   const int last_row = min(rb * BM + BM - 1, P.s - 1);
   const int ntile = last_row / BN + 1;
-  TileMap<D> map;
-  map.init(tid, gstride, KP, true);
-  TileBuf<D> kbuf, vbuf;
+  DmaMap<D> map;
+  map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
   const uint16_t* vg = v + base;
-  tile_fetch(kbuf, map, kg, gstride, P.s, tid);
-  tile_fetch(vbuf, map, vg, gstride, P.s, tid);
+  if (P.s >= BN) {
+    dma_tile<D>(map, kg, smem, wave);
+    dma_tile<D>(map, vg, smem + TILE, wave);
+  } else {
+    dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
+    dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
+  }
   for (int jt = 0; jt < ntile; ++jt) {
     const int j0 = jt * BN;
-    __syncthreads();
-    tile_commit(kbuf, map, Ks);
-    tile_commit(vbuf, map, Vs);
-    __syncthreads();
+    __syncthreads();  // tile jt has landed (every wave waited for its own loads); nobody reads the other stage any more
     if (jt + 1 < ntile) {
-      tile_fetch(kbuf, map, kg + (int64_t)(j0 + BN) * gstride, gstride, P.s - (j0 + BN), tid);
-      tile_fetch(vbuf, map, vg + (int64_t)(j0 + BN) * gstride, gstride, P.s - (j0 + BN), tid);
+      uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
+      const int left = P.s - (j0 + BN);
+      if (left >= BN) {
+        dma_tile<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave);
+        dma_tile<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave);
+      } else {
+        dma_tile_ragged<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave, lane, gstride, left);
+        dma_tile_ragged<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave, lane, gstride, left);
+      }
     }
+    const uint16_t* Ks = smem + (jt & 1) * 2 * TILE;
+    const uint16_t* Vs = Ks + TILE;
     const int j0w = j0 + 32 * ks;
     if (j0w <= iw0 + 31) {
       const bool diag = (j0w + 31 > iw0);
@@ -246,6 +267,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
         st = mfma32(ld_frag(Ks + (32 * ks + li) * KP + 16 * kc + 8 * hh), qf[kc], st);
         dd = mfma32(ld_frag(Vs + (32 * ks + li) * KP + 16 * kc + 8 * hh), dof[kc], dd);
       }
+      if (diag) {  // uniform per wave: keys j > i get probability exp2(-inf) = 0
+        asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+      }
       bf16x8_t dsf[2];
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
@@ -254,8 +281,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
         float ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          const float pex = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          const float pe = (diag && (jc + e > i)) ? 0.f : pex;
+          const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
           const float dp = ((keep >> e) & 1u) ? dd[8 * c + e] * P.keep_scale : 0.f;
           ds[e] = pe * (dp - dl);
         }

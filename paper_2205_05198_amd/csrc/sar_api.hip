@@ -56,7 +56,7 @@ sar_status check_attn_desc(const sar_attn_desc* c, sar::AttnParams* P) {
   return SAR_OK;
 }
 
-bool use_mfma(const sar_attn_desc* c, const sar::AttnParams& P) { return c->dtype == SAR_BF16 && sar::attn_mfma_supported(P.d); }
+bool use_mfma(const sar_attn_desc* c, const sar::AttnParams& P) { return c->dtype == SAR_BF16 && sar::attn_mfma_supported(P.d) && c->scale > 0.f; }
 
 sar_status check_simple_limits(const sar::AttnParams& P) {
   if (sar::attn_simple_lds_bytes(P.s) > 160 * 1024) return fail(SAR_ERR_UNSUPPORTED, "s (%d) too long for this dtype / head dimension", P.s);
