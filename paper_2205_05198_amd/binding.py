@@ -22,7 +22,7 @@ _SOURCES = {
     "attn_mfma_cols.hip": [],
     "rows.hip": [],
 }
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 SAR_F32, SAR_BF16 = 0, 1
 

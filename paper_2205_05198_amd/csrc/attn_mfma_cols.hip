@@ -18,12 +18,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
                                                                 const uint16_t* __restrict__ dO, const float* __restrict__ delta,
                                                                 uint16_t* __restrict__ dk, uint16_t* __restrict__ dv) {
   constexpr int BN = 64, BI = 64, KP = D + 8, KC = D / 16, DT = D / 32;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * 64 * KP];
-  __shared__ float lse_s[BI], delta_s[BI];
-  uint16_t* Ksm = smem;                 // this workgroup's keys, rows swapped inside groups of 32
-  uint16_t* Vsm = smem + 64 * KP;
-  uint16_t* Qs = smem + 2 * 64 * KP;    // current 64 query rows, natural order
-  uint16_t* dOs = smem + 3 * 64 * KP;
+  constexpr int TILE = 64 * KP;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[6 * TILE];
+  __shared__ float lse_s[2][BI], delta_s[2][BI];
+  uint16_t* Ksm = smem;          // this workgroup's keys, rows swapped inside groups of 32
+  uint16_t* Vsm = smem + TILE;
+  uint16_t* stages = smem + 2 * TILE;  // two stages of (Q, dO): 64 query rows each, natural order; global -> LDS directly
 
   const int N = P.b * P.A;
   const int kb = (int)(blockIdx.x / N);  // key block 0 sweeps the most rows: heaviest first
@@ -34,19 +34,44 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
   const int gstride = (int)P.stride_s;
   const int jw0 = kb * BN + kgp * 32;  // first key of this wave
 
-  TileMap<D> map;
-  map.init(tid, gstride, KP, true);
+  const int nit = (P.s + BI - 1) / BI;
+  const int it0 = kb;  // BI == BN: the first tile with rows >= this block's keys
+  const uint16_t* qg = q + base;
+  const uint16_t* dog = dO + base;
+  DmaMap<D> map;
   {
-    TileBuf<D> kbuf, vbuf;
-    tile_fetch(kbuf, map, k + base + (int64_t)(kb * BN) * gstride, gstride, P.s - kb * BN, tid);
-    tile_fetch(vbuf, map, v + base + (int64_t)(kb * BN) * gstride, gstride, P.s - kb * BN, tid);
-    tile_commit(kbuf, map, Ksm);
-    tile_commit(vbuf, map, Vsm);
+    const int left = P.s - kb * BN;
+    map.init(wave, lane, gstride, true, left);
+    dma_tile<D>(map, k + base + (int64_t)(kb * BN) * gstride, Ksm, wave);
+    dma_tile<D>(map, v + base + (int64_t)(kb * BN) * gstride, Vsm, wave);
+    map.init(wave, lane, gstride, false);
+    if (left >= BI) {
+      dma_tile<D>(map, qg + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE, wave);
+      dma_tile<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave);
+    } else {
+      dma_tile_ragged<D>(map, qg + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE, wave, lane, gstride, left);
+      dma_tile_ragged<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave, lane, gstride, left);
+    }
   }
-  map.init(tid, gstride, KP, false);
+  if (tid < BI) {
+    const int ir = min(it0 * BI + tid, P.s - 1);
+    lse_s[it0 & 1][tid] = lse[(size_t)bn * P.s + ir] * kLog2e;
+    delta_s[it0 & 1][tid] = delta[(size_t)bn * P.s + ir];
+  }
   // A operands of S^T and dD^T: LDS row 32*kgp + li holds key jw0 + perm_row(li)
   const uint16_t* kw = Ksm + (32 * kgp + li) * KP + 8 * hh;
   const uint16_t* vw = Vsm + (32 * kgp + li) * KP + 8 * hh;
+#ifdef SAR_KV_REGS
+  bf16x8_t kf[KC], vf[KC];
+  {
+    const int64_t off = base + (int64_t)min(jw0 + perm_row(li), P.s - 1) * P.stride_s + 8 * hh;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      kf[kc] = ld_frag(k + off + 16 * kc);
+      vf[kc] = ld_frag(v + off + 16 * kc);
+    }
+  }
+#endif
   // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
   bf16x8_t ident[2];
 #pragma unroll
@@ -64,38 +89,31 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
 
   const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
   const float sc2 = P.scale * kLog2e;
-  const int nit = (P.s + BI - 1) / BI;
-  const int it0 = kb;  // BI == BN: the first tile with rows >= this block's keys
-  const uint16_t* qg = q + base;
-  const uint16_t* dog = dO + base;
-  TileBuf<D> qbuf, dobuf;
-  float lse_n = 0.f, delta_n = 0.f;
-  tile_fetch(qbuf, map, qg + (int64_t)(it0 * BI) * gstride, gstride, P.s - it0 * BI, tid);
-  tile_fetch(dobuf, map, dog + (int64_t)(it0 * BI) * gstride, gstride, P.s - it0 * BI, tid);
-  if (tid < BI) {
-    const int ir = min(it0 * BI + tid, P.s - 1);
-    lse_n = lse[(size_t)bn * P.s + ir];
-    delta_n = delta[(size_t)bn * P.s + ir];
-  }
   for (int it = it0; it < nit; ++it) {
     const int i0 = it * BI;
-    __syncthreads();
-    tile_commit(qbuf, map, Qs);
-    tile_commit(dobuf, map, dOs);
-    if (tid < BI) {
-      lse_s[tid] = lse_n * kLog2e;
-      delta_s[tid] = delta_n;
-    }
-    __syncthreads();
-    if (it + 1 < nit) {  // next tile's global loads fly while this one is computed
-      tile_fetch(qbuf, map, qg + (int64_t)(i0 + BI) * gstride, gstride, P.s - (i0 + BI), tid);
-      tile_fetch(dobuf, map, dog + (int64_t)(i0 + BI) * gstride, gstride, P.s - (i0 + BI), tid);
+    dma_wait();       // this wave's share of tile `it` (and, the first time, of K and V) has landed
+    __syncthreads();  // ... and everybody's; nobody reads the other stage any more
+    float lse_n = 0.f, delta_n = 0.f;
+    if (it + 1 < nit) {  // next tile's loads fly while this one is computed
+      uint16_t* nxt = stages + ((it + 1) & 1) * 2 * TILE;
+      const int left = P.s - (i0 + BI);
+      if (left >= BI) {
+        dma_tile<D>(map, qg + (int64_t)(i0 + BI) * gstride, nxt, wave);
+        dma_tile<D>(map, dog + (int64_t)(i0 + BI) * gstride, nxt + TILE, wave);
+      } else {
+        dma_tile_ragged<D>(map, qg + (int64_t)(i0 + BI) * gstride, nxt, wave, lane, gstride, left);
+        dma_tile_ragged<D>(map, dog + (int64_t)(i0 + BI) * gstride, nxt + TILE, wave, lane, gstride, left);
+      }
       if (tid < BI) {
         const int ir = min(i0 + BI + tid, P.s - 1);
         lse_n = lse[(size_t)bn * P.s + ir];
         delta_n = delta[(size_t)bn * P.s + ir];
       }
     }
+    const uint16_t* Qs = stages + (it & 1) * 2 * TILE;
+    const uint16_t* dOs = Qs + TILE;
+    const float* lse_c = lse_s[it & 1];
+    const float* delta_c = delta_s[it & 1];
     const int i0w = i0 + 32 * is;  // this wave's 32 rows
     if (i0w + 31 >= jw0) {         // otherwise every row precedes this wave's keys
       const bool diag = (i0w < jw0 + 31);
@@ -104,11 +122,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
+#ifdef SAR_KV_REGS
+        st = mfma32(kf[kc], ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
+        dd = mfma32(vf[kc], ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
+#else
         st = mfma32(ld_frag(kw + 16 * kc), ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
         dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
+#endif
       }
       const int i = i0w + li;
-      const float lse2 = lse_s[32 * is + li], dl = delta_s[32 * is + li];
+      const float lse2 = lse_c[32 * is + li], dl = delta_c[32 * is + li];
       const uint64_t rowG = headG + (uint64_t)min(i, P.s - 1) * (uint64_t)(P.s >> 3);
       if (diag || i0w + 31 >= P.s) {  // uniform per wave: keys j > i and rows past the end get probability exp2(-inf) = 0
         asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
@@ -153,6 +176,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
           dkacc[dt] = mfma32(ld_frag_tr_perm(Qs, KP, 32 * is + 16 * X, 32 * dt, lane), sT, dkacc[dt]);
         }
       }
+    }
+    if (it + 1 < nit && tid < BI) {  // the other stage's row statistics: last read in the previous step
+      lse_s[(it + 1) & 1][tid] = lse_n * kLog2e;
+      delta_s[(it + 1) & 1][tid] = delta_n;
     }
     // Keep the loop-carried accumulators in the accumulation registers (AGPRs) across the back-edge; without
     // this the compiler copies all of them to VGPRs and back on every trip.

@@ -87,14 +87,31 @@ __device__ __forceinline__ void tile_commit(const TileBuf<D>& buf, const TileMap
 
 // ---------------------------------------------------------------------------------------------------
 // Direct global -> LDS tile loads (global_load_lds_dwordx4): lane L of a wave-wide load writes its 16 bytes
-// at (wave-uniform LDS base) + 16 L, without passing through registers.  A tile of 64 rows whose LDS pitch
-// is D + 8 elements = CPR + 1 chunks of 16 bytes (the last chunk of a row is padding) is exactly CPR + 1
+// at (wave-uniform LDS base, in M0) + 16 L, without passing through registers.  A tile of 64 rows whose LDS
+// pitch is D + 8 elements = CPR + 1 chunks of 16 bytes (the last chunk of a row is padding) is exactly CPR + 1
 // such loads of 64 consecutive chunks; wave w of the workgroup issues loads w, w + 4, ...  Lanes that fall
 // on a padding chunk re-read the row's last chunk.  Several tiles with the same row stride (K and V, or Q and
-// dO) share one offset table.  Completion: vmcnt of the issuing wave, then a workgroup barrier.
+// dO) share one offset table.
+//
+// The load is written as inline assembly on purpose.  Through the compiler's builtin every later LDS read is
+// preceded by a wait for ALL outstanding direct loads (the compiler cannot tell the stage being filled from the
+// stage being read), which serialises the pipeline.  The price: the compiler does not know about these loads, so
+// the kernels wait for them explicitly (dma_wait) before the barrier that publishes a stage.
 // ---------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void_t;
-typedef __attribute__((address_space(1))) const void glb_void_t;
+
+__device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_void_t*)p; }
+__device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "m0");
+}
+// Same, pinned in the instruction stream: issued after `token` has been computed and before anything that uses
+// `token` afterwards (the statement pretends to modify it).
+template <typename T>
+__device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base, T& token) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : "+v"(token) : "v"(gaddr), "s"(lds_base) : "m0");
+}
+// every direct load this wave has issued has landed in LDS
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <int D>
 struct DmaMap {
@@ -115,14 +132,28 @@ struct DmaMap {
   }
 };
 
-// gtile: first row of the tile in global memory (uniform); lds: the tile's place in LDS (uniform)
+// gtile: first row of the tile in global memory (uniform); lds: the tile's place in LDS (uniform).
+// dma_one issues round u (0 .. PER-1) of this wave's loads, so that callers can spread them between matrix
+// instructions: the texture path accepts one such load every 16 cycles per CU, and a wave that issues its whole
+// share back to back stalls until they are accepted.
+template <int D>
+__device__ __forceinline__ void dma_one(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, int u) {
+  const int l = wave + 4 * u;
+  if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)  // only the last round can run past the tile
+    dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l);
+}
 template <int D>
 __device__ __forceinline__ void dma_tile(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave) {
 #pragma unroll
+  for (int u = 0; u < DmaMap<D>::PER; ++u) dma_one<D>(map, gtile, lds, wave, u);
+}
+template <int D, typename T>
+__device__ __forceinline__ void dma_tile(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, T& token) {
+#pragma unroll
   for (int u = 0; u < DmaMap<D>::PER; ++u) {
     const int l = wave + 4 * u;
-    if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)  // only the last round can run past the tile
-      __builtin_amdgcn_global_load_lds((glb_void_t*)(reinterpret_cast<const char*>(gtile) + map.goff[u]), (lds_void_t*)(lds + 512 * l), 16, 0, 0);
+    if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)
+      dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l, token);
   }
 }
 // the same for a tile that ends before its 64th row: offsets recomputed with clamped rows

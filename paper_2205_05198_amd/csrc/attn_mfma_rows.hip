@@ -23,6 +23,7 @@
 //                                               dS / D moved to the transposed layout by an identity MFMA)
 // No s x s tensor is ever written; the dropout mask is regenerated from (seed, offset) in all three.
 #include "attn_mfma_common.h"
+#include <type_traits>
 
 namespace sar {
 
@@ -30,15 +31,21 @@ static constexpr float kLazyRescale = 60.0f;  // the running reference exponent 
 
 // ===================================================================================================
 // Forward.  Workgroup = 64 query rows: wave = (rg, ks), rg = 32-row group, ks = which 32 keys of each 64-key
-// tile.  K and V tiles (both with swapped rows) go from global memory straight into one of two LDS stages;
-// the loads of tile j+1 are issued right after the single barrier of step j and land while tile j is computed.
+// tile.  K and V tiles (both with swapped rows) go from global memory straight into LDS, two stages each.
+// The score tile runs one step ahead of the rest: step j computes S_{j+1} (matrix core + LDS reads) in the same
+// basic block as the softmax / dropout arithmetic of tile j (vector ALU) and the product P_j V_j, so that the
+// instruction scheduler can overlap the three.  Everything that needs a branch sits at the ends of a step: the
+// causal mask only exists in the variants of the step that produce the diagonal tile, and the (rare) rescaling
+// of the running maximum for tile j+1 is decided at the end of step j.
 // ===================================================================================================
 template <int D>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
   constexpr int BM = 64, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
   constexpr int TILE = BN * KP;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];  // stage 0: K, V; stage 1: K, V
+  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];
+  uint16_t* Kst = smem;             // K tile jt lives in Kst + (jt & 1) * TILE
+  uint16_t* Vst = smem + 2 * TILE;  // V tile jt lives in Vst + (jt & 1) * TILE
 
   const int N = P.b * P.A;
   const int nrb = (P.s + BM - 1) / BM;
@@ -55,6 +62,10 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   bf16x8_t qf[KC];
 #pragma unroll
   for (int kc = 0; kc < KC; ++kc) qf[kc] = ld_frag(q + base + (int64_t)i_ld * P.stride_s + 16 * kc + 8 * hh);
+  // These must have arrived before the tile loop: a wait left inside the loop would also wait for the direct
+  // loads in flight there, which the compiler does not know about.
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[kc]));
 
   // Philox call index of (row i, key 0): offset + e/8 with e = ((beta*a + head)*s + i)*s
   const uint64_t rowG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s + (uint64_t)i_ld) * (uint64_t)(P.s >> 3);
@@ -64,59 +75,92 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
-  float m_ref = -INFINITY, l_run = 0.f;
+  float l_run = 0.f;
   const float sc2 = P.scale * kLog2e;
 
   const int last_row = min(rb * BM + BM - 1, P.s - 1);
-  const int ntile = last_row / BN + 1;
+  const int ntile = last_row / BN + 1;  // the last tile is the one on the diagonal
   DmaMap<D> map;
   map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
   const uint16_t* vg = v + base;
-  if (P.s >= BN) {
-    dma_tile<D>(map, kg, smem, wave);
-    dma_tile<D>(map, vg, smem + TILE, wave);
-  } else {
-    dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
-    dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
-  }
-  for (int jt = 0; jt < ntile; ++jt) {
-    const int j0 = jt * BN;
-    __syncthreads();  // tile jt has landed (every wave waited for its own loads); nobody reads the other stage any more
-    if (jt + 1 < ntile) {
-      uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
-      const int left = P.s - (j0 + BN);
-      if (left >= BN) {
-        dma_tile<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave);
-        dma_tile<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave);
-      } else {
-        dma_tile_ragged<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave, lane, gstride, left);
-        dma_tile_ragged<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave, lane, gstride, left);
-      }
+  auto load_tile = [&](const uint16_t* g, uint16_t* st2, int jt) __attribute__((always_inline)) {
+    const int left = P.s - jt * BN;  // only the last tile of the sequence can end before its 64th row
+    if (left >= BN) dma_tile<D>(map, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, wave);
+    else dma_tile_ragged<D>(map, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, wave, lane, gstride, left);
+  };
+  // S^T tile of this wave's 32 keys of tile jt against its 32 rows; st[8*c + e] is the score of key
+  // jt*64 + 32*ks + 16*c + 8*hh + e.  DIAG: the tile touches the diagonal, keys j > i are masked.
+  auto scores = [&](const int jt, auto diag) __attribute__((always_inline)) {
+    const uint16_t* Ks = Kst + (jt & 1) * TILE;
+    float16_t st;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) st[e] = 0.f;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) st = mfma32(ld_frag(Ks + (32 * ks + li) * KP + 16 * kc + 8 * hh), qf[kc], st);
+    if (decltype(diag)::value) {
+      const int j0w = jt * BN + 32 * ks;
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
     }
-    const uint16_t* Ks = smem + (jt & 1) * 2 * TILE;
-    const uint16_t* Vs = Ks + TILE;
-    const int j0w = j0 + 32 * ks;  // this wave's 32 keys
-    if (j0w <= iw0 + 31) {
-      // ---- S^T = K Q^T ----
-      float16_t st;
+    return st;
+  };
+  // row maximum of a score tile in the softmax's units (alpha*log2(e)*score; alpha > 0), floored so that a fully
+  // masked tile (the upper wave of the first row group on the diagonal) stays finite
+  auto tile_max = [&](const float16_t& st) __attribute__((always_inline)) {
+    float mt = fmaxf(fmaxf(st[0], st[1]), st[2]);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) st[e] = 0.f;
+    for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, st[e]), st[e + 1]);
+    mt = fmaxf(mt, st[15]);
+    return fmaxf(fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2, -1.0e30f);
+  };
+
+  load_tile(kg, Kst, 0);
+  load_tile(vg, Vst, 0);
+  if (ntile > 1) load_tile(kg, Kst, 1);
+  dma_wait();
+  __syncthreads();
+  float16_t st = ntile == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
+  float m_ref = tile_max(st);
+
+  // One step: tile jt's softmax, dropout and P V, and (NEXT != 0) the scores of tile jt+1; NEXT == 2: that tile is
+  // the diagonal one.
+  auto step = [&](const int jt, auto next) __attribute__((always_inline)) {
+    constexpr int NEXT = decltype(next)::value;
+    dma_wait();       // this wave's loads of K tile jt+1 and V tile jt have landed
+    __syncthreads();  // ... and everybody's; nobody reads K tile jt or V tile jt-1 any more
+    if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
+    if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
+    const uint16_t* Vs = Vst + (jt & 1) * TILE;
+    const int j0w = jt * BN + 32 * ks;
+    float16_t stn;
+    if (NEXT == 1) stn = scores(jt + 1, std::false_type{});
+    if (NEXT == 2) stn = scores(jt + 1, std::true_type{});
+    float psum = 0.f;
+    bf16x8_t pf[2];
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) st = mfma32(ld_frag(Ks + (32 * ks + li) * KP + 16 * kc + 8 * hh), qf[kc], st);
-      // st[8*c + e] is the score of key j0w + 16*c + 8*hh + e against query row i
-      if (j0w + 31 > iw0) {  // tile touches the diagonal (uniform per wave): mask keys j > i
-        asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
+    for (int c = 0; c < 2; ++c) {
+      const Philox4 rnd = philox_call8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1);
+      float pd[8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+      for (int e = 0; e < 8; ++e) {
+        const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
+        psum += pe;
+        pd[e] = keep_field(rnd, e, P.thresh) ? pe : 0.f;
       }
-      // the softmax runs on alpha*log2(e)*score; alpha > 0, so the maximum can be taken on the raw scores
-      float mt = fmaxf(fmaxf(st[0], st[1]), st[2]);
+      pf[c] = pack8(pd);
+    }
+    l_run += psum;
+    // ---- O^T += V^T P^T ----
 #pragma unroll
-      for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, st[e]), st[e + 1]);
-      mt = fmaxf(mt, st[15]);
-      mt = fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2;
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) oacc[dt] = mfma32(ld_frag_tr_perm(Vs, KP, 32 * ks + 16 * c, 32 * dt, lane), pf[c], oacc[dt]);
+    if (NEXT != 0) {
+      st = stn;
+      // the running reference exponent only moves when the next tile's maximum exceeds it by more than 2^60
+      const float mt = tile_max(stn);
       if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale) != 0, 0)) {
         const float m_new = fmaxf(m_ref, mt);
         const float corr = __builtin_amdgcn_exp2f(m_ref - m_new);
@@ -127,27 +171,13 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
 #pragma unroll
           for (int e = 0; e < 16; ++e) oacc[dt][e] *= corr;
       }
-      float psum = 0.f;
-      bf16x8_t pf[2];
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const uint32_t keep = keep_bits8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1, P.thresh);
-        float pd[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
-          psum += pe;
-          pd[e] = ((keep >> e) & 1u) ? pe : 0.f;
-        }
-        pf[c] = pack8(pd);
-      }
-      l_run += psum;
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) oacc[dt] = mfma32(ld_frag_tr_perm(Vs, KP, 32 * ks + 16 * c, 32 * dt, lane), pf[c], oacc[dt]);
     }
+  };
+  {
+    int jt = 0;
+    for (; jt + 2 < ntile; ++jt) step(jt, std::integral_constant<int, 1>{});
+    if (jt + 1 < ntile) step(jt++, std::integral_constant<int, 2>{});
+    step(jt, std::integral_constant<int, 0>{});
   }
 
   // ---- merge the two key halves of each row group, then O = O^T^T / ((1-p) l), LSE = m + ln l ----
@@ -215,6 +245,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
     dof[kc] = ld_frag(dO + off);
     dpart += dot8(dof[kc], ld_frag(o + off));
   }
+  // These must have arrived before the tile loop: a wait left inside the loop would also wait for the direct
+  // loads in flight there, which the compiler does not know about.
+#pragma unroll
+  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[kc]), "+v"(dof[kc]));
   const float dl = dpart + __shfl_xor(dpart, 32, 64);
   if (ks == 0 && hh == 0 && i < P.s) delta[(size_t)bn * P.s + i] = dl;
   const float lse2 = lse[(size_t)bn * P.s + i_ld] * kLog2e;
@@ -240,22 +274,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
     dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
     dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
   }
-  for (int jt = 0; jt < ntile; ++jt) {
+  // One tile step.  MODE says how tile jt+1 is loaded into the other stage meanwhile: 0 = there is none,
+  // 1 = loads spread between the matrix instructions below, 2 = the next tile ends before its 64th row: loads with
+  // clamped rows, all issued up front.
+  auto step = [&](const int jt, auto mode) __attribute__((always_inline)) {
+    constexpr int MODE = decltype(mode)::value;
     const int j0 = jt * BN;
-    __syncthreads();  // tile jt has landed (every wave waited for its own loads); nobody reads the other stage any more
-    if (jt + 1 < ntile) {
-      uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
-      const int left = P.s - (j0 + BN);
-      if (left >= BN) {
-        dma_tile<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave);
-        dma_tile<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave);
-      } else {
-        dma_tile_ragged<D>(map, kg + (int64_t)(j0 + BN) * gstride, nxt, wave, lane, gstride, left);
-        dma_tile_ragged<D>(map, vg + (int64_t)(j0 + BN) * gstride, nxt + TILE, wave, lane, gstride, left);
-      }
+    dma_wait();       // this wave's share of tile jt has landed
+    __syncthreads();  // ... and everybody's; nobody reads the other stage any more
+    uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
+    const uint16_t* kn = kg + (int64_t)(j0 + BN) * gstride;
+    const uint16_t* vn = vg + (int64_t)(j0 + BN) * gstride;
+    if (MODE == 2) {
+      dma_tile_ragged<D>(map, kn, nxt, wave, lane, gstride, P.s - (j0 + BN));
+      dma_tile_ragged<D>(map, vn, nxt + TILE, wave, lane, gstride, P.s - (j0 + BN));
     }
     const uint16_t* Ks = smem + (jt & 1) * 2 * TILE;
     const uint16_t* Vs = Ks + TILE;
+    // MODE 1: the four waves issue their shares of the next tile's loads at four different points of the step
+    if (MODE == 1 && wave == 0) {
+      dma_tile<D>(map, kn, nxt, wave);
+      dma_tile<D>(map, vn, nxt + TILE, wave);
+    }
     const int j0w = j0 + 32 * ks;
     if (j0w <= iw0 + 31) {
       const bool diag = (j0w + 31 > iw0);
@@ -273,16 +313,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
         for (int e = 0; e < 16; ++e)
           if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
       }
+      if (MODE == 1 && wave == 1) {  // pinned after the score tile
+        float tok = st[0];
+        dma_tile<D>(map, kn, nxt, wave, tok);
+        dma_tile<D>(map, vn, nxt + TILE, wave, tok);
+        st[0] = tok;
+      }
       bf16x8_t dsf[2];
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int jc = j0w + 16 * c + 8 * hh;
-        const uint32_t keep = keep_bits8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1, P.thresh);
+        Philox4 rnd = philox_call8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1);
+        // waves 2 and 3 issue their loads of the next tile after the first / second random-number block
+        if (MODE == 1 && wave == 2 + c) {
+          dma_tile<D>(map, kn, nxt, wave, rnd.x);
+          dma_tile<D>(map, vn, nxt + TILE, wave, rnd.x);
+        }
         float ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          const float dp = ((keep >> e) & 1u) ? dd[8 * c + e] * P.keep_scale : 0.f;
+          const float dp = keep_field(rnd, e, P.thresh) ? dd[8 * c + e] * P.keep_scale : 0.f;
           ds[e] = pe * (dp - dl);
         }
         dsf[c] = pack8(ds);
@@ -291,7 +342,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) dqacc[dt] = mfma32(ld_frag_tr_perm(Ks, KP, 32 * ks + 16 * c, 32 * dt, lane), dsf[c], dqacc[dt]);
+    } else if (MODE == 1 && wave != 0) {
+      dma_tile<D>(map, kn, nxt, wave);
+      dma_tile<D>(map, vn, nxt + TILE, wave);
     }
+  };
+  {
+    const bool last_full = P.s - (ntile - 1) * BN >= BN;  // only the last tile can be ragged
+    const int nspread = last_full ? ntile - 1 : ntile - 2;
+    int jt = 0;
+    for (; jt < nspread; ++jt) step(jt, std::integral_constant<int, 1>{});
+    if (jt + 1 < ntile) step(jt++, std::integral_constant<int, 2>{});
+    step(jt, std::integral_constant<int, 0>{});
   }
   // ---- sum the two key halves, scale, store ----
   __syncthreads();

@@ -74,6 +74,14 @@ __device__ __forceinline__ uint32_t keep_bits8(uint64_t G, uint32_t site, uint32
   m |= ((o.w >> 16) >= T) ? 128u : 0u;
   return m;
 }
+// the same decision for element r (0..7) of one call, straight from the raw output words
+__device__ __forceinline__ Philox4 philox_call8(uint64_t G, uint32_t site, uint32_t k0, uint32_t k1) {
+  return philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), 0u, site, k0, k1);
+}
+__device__ __forceinline__ bool keep_field(const Philox4& o, int r, uint32_t T) {
+  const uint32_t w = (r >> 1) == 0 ? o.x : (r >> 1) == 1 ? o.y : (r >> 1) == 2 ? o.z : o.w;
+  return ((r & 1) ? (w >> 16) : (w & 0xFFFFu)) >= T;
+}
 // keep bit of a single element e
 __device__ __forceinline__ uint32_t keep_bit1(uint64_t e, uint64_t offset, uint32_t site, uint32_t k0, uint32_t k1, uint32_t T) {
   uint32_t m = keep_bits8(offset + (e >> 3), site, k0, k1, T);
