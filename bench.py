@@ -135,6 +135,28 @@ def main():
         except Exception:
             traffic = None
 
+    # kernels next to the hot path (not part of a step): fused bias-dropout-add -> LayerNorm forward, and the
+    # backward of bias-dropout-add with its bias gradient; HIP events around 50 launches each
+    def timed(fn, n=50):
+        for _ in range(5):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(n):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / n
+    dbias = torch.empty(h, dtype=torch.float32, device="cuda")
+    ws3 = torch.empty(max(16, sar.bias_dropout_add_bwd_workspace(rdesc)), dtype=torch.uint8, device="cuda")
+    extra_ms = {
+        "bias_dropout_add_ln_fwd": timed(lambda: sar.bias_dropout_add_ln_fwd(rdesc, x, bias, resid, gamma, beta, out, y, mean, rstd)),
+        "bias_dropout_add_bwd": timed(lambda: sar.bias_dropout_add_bwd(rdesc, dy, dx, dbias, ws3)),
+    }
+    extra_bytes = {"bias_dropout_add_ln_fwd": rows * h * 4 * esz + 8 * rows + 3 * esz * h,   # read x, resid; write out, y
+                   "bias_dropout_add_bwd": rows * h * 2 * esz + 4 * h}                        # read dout; write dx, dbias
+
     # stored-activation baseline (Section 4.1) for the recompute-vs-stored ratio
     stored = None
     if args.stored_steps > 0:
@@ -193,6 +215,8 @@ def main():
                          "tflops_executed_18dTN": 18 * d * T * N / (attn_ms * 1e-3) / 1e12},
         "rows_kernels_gbs": {n: bytes_alg[n] / (kern_ms[n] * 1e-3) / 1e9 for n in bytes_alg},
         "rows_kernels_frac_hbm_peak": {n: bytes_alg[n] / (kern_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS for n in bytes_alg},
+        "next_rows_kernels": {n: {"ms": extra_ms[n], "gbs": extra_bytes[n] / (extra_ms[n] * 1e-3) / 1e9,
+                                  "frac_hbm_peak": extra_bytes[n] / (extra_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS} for n in extra_ms},
         "stored_baseline": stored,
         "paper_context": {"full_recompute_overhead_pct": "30-40", "mfu_530B_2240_A100_pct": 54.2},
     }

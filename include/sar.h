@@ -177,6 +177,31 @@ sar_status ln_bwd(const sar_rows_desc* desc, const void* dy, const void* x, cons
 sar_status bias_dropout_add(const sar_rows_desc* desc, const void* x, const void* bias, const void* resid,
                             void* out, uint8_t* mask_out, void* stream);
 
+/*
+ * bias_dropout_add_ln_fwd -- the step above fused with the LayerNorm that consumes it (Eq. 3: the last line of
+ * one block feeds the first line of the next), one pass over the row instead of two:
+ *   out = resid + M o (x + bias) / (1 - p),   y = LayerNorm(out) with gamma, beta, eps.
+ *   x, resid [rows, h], bias [h] or NULL, gamma, beta [h] : in;  out, y [rows, h] : out (desc->dtype);
+ *   mean, rstd [rows] : out, float, the statistics of `out` as stored (so ln_bwd on the stored row matches).
+ *   out may alias resid; y may alias nothing.  Same Philox stream as bias_dropout_add (site 1).
+ */
+sar_status bias_dropout_add_ln_fwd(const sar_rows_desc* desc, const void* x, const void* bias, const void* resid,
+                                   const void* gamma, const void* beta, void* out, void* y, float* mean, float* rstd,
+                                   void* stream);
+
+/* Bytes of scratch bias_dropout_add_bwd needs when dbias is requested (row-split partial sums; may be 0). */
+size_t bias_dropout_add_bwd_workspace(const sar_rows_desc* desc);
+
+/*
+ * bias_dropout_add_bwd -- gradient of bias_dropout_add (Eq. 3, last line): the mask is regenerated from
+ * (seed, offset), nothing of the forward is needed.
+ *   dout [rows, h] : in;  dx = M o dout / (1 - p) [rows, h] : out (desc->dtype; may alias dout)
+ *   dbias [h] : out, float, column sums of dx over this rank's rows, or NULL (then no workspace is needed).
+ *   The gradient of the residual branch is dout itself and is not written.
+ */
+sar_status bias_dropout_add_bwd(const sar_rows_desc* desc, const void* dout, void* dx, float* dbias,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 /* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
 const char* sar_last_error(void);
 

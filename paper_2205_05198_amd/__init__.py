@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     AttnDesc, RowsDesc, SarError, attn_core_bwd_recompute, attn_core_bwd_recompute_dkdv, attn_core_bwd_recompute_dq,
     attn_core_bwd_stored, attn_core_bwd_workspace,
     attn_core_fwd, attn_core_fwd_stored, attn_core_philox_count, attn_core_saved_bytes,
-    attn_core_small_buffer_bytes, bias_dropout_add, build_library, library_path, ln_bwd, ln_bwd_workspace,
+    attn_core_small_buffer_bytes, bias_dropout_add, bias_dropout_add_bwd, bias_dropout_add_bwd_workspace,
+    bias_dropout_add_ln_fwd, build_library, library_path, ln_bwd, ln_bwd_workspace,
     ln_fwd, load_library, sar_last_error,
 )

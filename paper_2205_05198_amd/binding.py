@@ -122,6 +122,9 @@ def load_library():
         "ln_bwd_workspace": (sz, [rd]),
         "ln_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "bias_dropout_add": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp]),
+        "bias_dropout_add_ln_fwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "bias_dropout_add_bwd_workspace": (sz, [rd]),
+        "bias_dropout_add_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, sz, vp]),
         "sar_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in protos.items():
@@ -134,7 +137,8 @@ def load_library():
 EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_recompute", "attn_core_bwd_recompute_dq",
            "attn_core_bwd_recompute_dkdv", "attn_core_fwd_stored",
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
-           "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "sar_last_error"]
+           "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
+           "bias_dropout_add_bwd_workspace", "bias_dropout_add_bwd", "sar_last_error"]
 
 
 def _ptr(t):
@@ -219,3 +223,17 @@ def ln_bwd(desc: RowsDesc, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, workspac
 
 def bias_dropout_add(desc: RowsDesc, x, bias, resid, out, mask_out=None):
     _check(load_library().bias_dropout_add(ctypes.byref(desc), _ptr(x), _ptr(bias), _ptr(resid), _ptr(out), _ptr(mask_out), _stream()))
+
+
+def bias_dropout_add_ln_fwd(desc: RowsDesc, x, bias, resid, gamma, beta, out, y, mean, rstd):
+    _check(load_library().bias_dropout_add_ln_fwd(ctypes.byref(desc), _ptr(x), _ptr(bias), _ptr(resid), _ptr(gamma), _ptr(beta), _ptr(out),
+                                                   _ptr(y), _ptr(mean), _ptr(rstd), _stream()))
+
+
+def bias_dropout_add_bwd_workspace(desc: RowsDesc) -> int:
+    return int(load_library().bias_dropout_add_bwd_workspace(ctypes.byref(desc)))
+
+
+def bias_dropout_add_bwd(desc: RowsDesc, dout, dx, dbias=None, workspace=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().bias_dropout_add_bwd(ctypes.byref(desc), _ptr(dout), _ptr(dx), _ptr(dbias), _ptr(workspace), nbytes, _stream()))

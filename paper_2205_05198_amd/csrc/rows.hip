@@ -231,6 +231,148 @@ __global__ __launch_bounds__(256) void bias_dropout_add_kernel(RowsParams P, con
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Fused bias-dropout-add + LayerNorm forward (last line of Eq. 3 feeding the next layer's first line):
+//   out = resid + M (x + bias)/(1-p),  y = LayerNorm(out).
+// One workgroup per row, as ln_fwd: the row is read once instead of twice (8 instead of 10 bytes per element).
+// The statistics are taken from `out` as it is stored (rounded to T), so that a later ln_bwd, which re-reads the
+// stored row, sees exactly the values mean and rstd belong to.
+// ---------------------------------------------------------------------------------------------------
+template <typename T, int VPT, bool HAS_BIAS>
+__global__ __launch_bounds__(1024) void bda_ln_fwd_kernel(RowsParams P, const T* __restrict__ x, const T* __restrict__ bias, const T* resid,
+                                                         const T* __restrict__ gamma, const T* __restrict__ beta, T* out, T* __restrict__ y,
+                                                         float* __restrict__ mean, float* __restrict__ rstd) {
+  __shared__ float red[32];
+  const int64_t r = blockIdx.x;
+  const int nchunk = (int)(P.h >> 3);
+  float ov[VPT][8];
+  float s1 = 0.f, s2 = 0.f, shift = 0.f;
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+      float xv[8], rv[8], bv[8];
+      Vec8<T>::load(x + r * P.h + 8 * c, xv);
+      Vec8<T>::load(resid + r * P.h + 8 * c, rv);
+      if (HAS_BIAS) Vec8<T>::load(bias + 8 * c, bv);
+      const uint64_t e = (uint64_t)(P.row_offset + r) * (uint64_t)P.h + (uint64_t)(8 * c);
+      const uint32_t keep = keep_bits8(P.offset + (e >> 3), 1u, P.key0, P.key1, P.thresh);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float xb = HAS_BIAS ? xv[q] + bv[q] : xv[q];
+        ov[u][q] = Elem<T>::round(((keep >> q) & 1u) ? fmaf(xb, P.keep_scale, rv[q]) : rv[q]);
+      }
+      Vec8<T>::store(out + r * P.h + 8 * c, ov[u]);
+    }
+  }
+  // shift = the row's first element, held by thread 0: broadcast through LDS
+  if (threadIdx.x == 0) red[0] = ov[0][0];
+  __syncthreads();
+  shift = red[0];
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const float dlt = ov[u][q] - shift;
+        s1 += dlt;
+        s2 = fmaf(dlt, dlt, s2);
+      }
+    }
+  }
+  block_sum2(s1, s2, red);
+  const float invh = 1.f / (float)P.h;
+  const float m1 = s1 * invh;
+  const float var = fmaxf(s2 * invh - m1 * m1, 0.f);
+  const float mu = shift + m1;
+  const float rs = rsqrtf(var + P.eps);
+#pragma unroll
+  for (int u = 0; u < VPT; ++u) {
+    const int c = threadIdx.x + u * blockDim.x;
+    if (c < nchunk) {
+      float g[8], bt[8], o[8];
+      Vec8<T>::load(gamma + 8 * c, g);
+      Vec8<T>::load(beta + 8 * c, bt);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) o[q] = fmaf((ov[u][q] - mu) * rs, g[q], bt[q]);
+      Vec8<T>::store(y + r * P.h + 8 * c, o);
+    }
+  }
+  if (threadIdx.x == 0) { mean[r] = mu; rstd[r] = rs; }
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bias-dropout-add backward: dx = M dout/(1-p) with M regenerated from Philox; the residual branch's gradient is
+// dout itself and is not written.  Without dbias this is elementwise (one thread per 8 elements).  With dbias
+// (the column sums of dx) a workgroup owns a slab of 64 columns and a range of rows, as ln_bwd's second pass:
+// part[split][h] partial sums, or dbias itself if there is one split.
+// ---------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void bda_bwd_kernel(RowsParams P, const T* __restrict__ dout, T* __restrict__ dx) {
+  const int64_t nchunk_row = P.h >> 3;
+  const int64_t total = P.rows * nchunk_row;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
+  float dv[8], o[8];
+  Vec8<T>::load(dout + r * P.h + c, dv);
+  const uint64_t e = (uint64_t)(P.row_offset + r) * (uint64_t)P.h + (uint64_t)c;
+  const uint32_t keep = keep_bits8(P.offset + (e >> 3), 1u, P.key0, P.key1, P.thresh);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) o[q] = ((keep >> q) & 1u) ? dv[q] * P.keep_scale : 0.f;
+  Vec8<T>::store(dx + r * P.h + c, o);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bda_bwd_slab_kernel(RowsParams P, const T* __restrict__ dout, T* __restrict__ dx, float* __restrict__ db_out,
+                                                          int rows_per_split) {
+  __shared__ float sb[32][65];
+  const int slab = blockIdx.x, split = blockIdx.y;
+  const int seg = threadIdx.x >> 3, l8 = threadIdx.x & 7;
+  const int64_t col = (int64_t)slab * 64 + 8 * l8;
+  const bool colok = col < P.h;
+  const int64_t r_lo = (int64_t)split * rows_per_split;
+  const int64_t r_hi = min(P.rows, r_lo + rows_per_split);
+  float ab[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ab[e] = 0.f;
+  for (int64_t r = r_lo + seg; r < r_hi; r += 32) {
+    if (colok) {
+      float dv[8], o[8];
+      Vec8<T>::load(dout + r * P.h + col, dv);
+      const uint64_t e = (uint64_t)(P.row_offset + r) * (uint64_t)P.h + (uint64_t)col;
+      const uint32_t keep = keep_bits8(P.offset + (e >> 3), 1u, P.key0, P.key1, P.thresh);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        o[q] = ((keep >> q) & 1u) ? dv[q] * P.keep_scale : 0.f;
+        ab[q] += o[q];
+      }
+      Vec8<T>::store(dx + r * P.h + col, o);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) sb[seg][8 * l8 + e] = ab[e];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int c = threadIdx.x;
+    float t = 0.f;
+    for (int q = 0; q < 32; ++q) t += sb[q][c];
+    const int64_t cc = (int64_t)slab * 64 + c;
+    if (cc < P.h) db_out[(size_t)split * P.h + cc] = t;
+  }
+}
+
+// sums row-split partials: part[nsplit][h] -> dbias[h]
+__global__ void bda_bwd_finish_kernel(const float* __restrict__ part, int nsplit, int64_t h, float* __restrict__ dbias) {
+  const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= h) return;
+  float t = 0.f;
+  for (int q = 0; q < nsplit; ++q) t += part[(size_t)q * h + c];
+  dbias[c] = t;
+}
+
 // ------------------------------------------------------------------------------------------------ launchers
 static inline int pick_vpt(int64_t h, int& threads) {
   const int nchunk = (int)(h >> 3);
@@ -335,6 +477,63 @@ static hipError_t bda_t(const RowsParams& P, const void* x, const void* bias, co
 hipError_t launch_bias_dropout_add(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, void* out, uint8_t* mask,
                                    hipStream_t st) {
   return bf16 ? bda_t<uint16_t>(P, x, bias, resid, out, mask, st) : bda_t<float>(P, x, bias, resid, out, mask, st);
+}
+
+template <typename T>
+static hipError_t bda_ln_t(const RowsParams& P, const void* x, const void* bias, const void* resid, const void* gamma, const void* beta, void* out,
+                           void* y, float* mean, float* rstd, hipStream_t st) {
+  int threads;
+  const int vpt = pick_vpt(P.h, threads);
+  dim3 grid((unsigned)P.rows), block(threads);
+#define SAR_BDA_LN(V, B) hipLaunchKernelGGL((bda_ln_fwd_kernel<T, V, B>), grid, block, 0, st, P, (const T*)x, (const T*)bias, (const T*)resid, \
+                                            (const T*)gamma, (const T*)beta, (T*)out, (T*)y, mean, rstd)
+#define SAR_BDA_LN_V(V) do { if (bias) SAR_BDA_LN(V, true); else SAR_BDA_LN(V, false); } while (0)
+  switch (vpt) {
+    case 1: SAR_BDA_LN_V(1); break;
+    case 2: SAR_BDA_LN_V(2); break;
+    case 3: SAR_BDA_LN_V(3); break;
+    default: SAR_BDA_LN_V(4); break;
+  }
+#undef SAR_BDA_LN_V
+#undef SAR_BDA_LN
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_dropout_add_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, const void* gamma,
+                                          const void* beta, void* out, void* y, float* mean, float* rstd, hipStream_t st) {
+  return bf16 ? bda_ln_t<uint16_t>(P, x, bias, resid, gamma, beta, out, y, mean, rstd, st)
+              : bda_ln_t<float>(P, x, bias, resid, gamma, beta, out, y, mean, rstd, st);
+}
+
+size_t bda_bwd_workspace_bytes(int64_t rows, int64_t h) {
+  int nslab, nsplit, rps;
+  ln_bwd_plan(rows, h, nslab, nsplit, rps);
+  return nsplit > 1 ? (size_t)nsplit * (size_t)h * sizeof(float) : 0;
+}
+
+template <typename T>
+static hipError_t bda_bwd_t(const RowsParams& P, const void* dout, void* dx, float* dbias, void* ws, hipStream_t st) {
+  if (!dbias) {
+    const int64_t total = P.rows * (P.h >> 3);
+    hipLaunchKernelGGL((bda_bwd_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P, (const T*)dout, (T*)dx);
+    return hipGetLastError();
+  }
+  int nslab, nsplit, rps;
+  ln_bwd_plan(P.rows, P.h, nslab, nsplit, rps);
+  if (nsplit == 1) {
+    hipLaunchKernelGGL((bda_bwd_slab_kernel<T>), dim3(nslab, 1), dim3(256), 0, st, P, (const T*)dout, (T*)dx, dbias, rps);
+    return hipGetLastError();
+  }
+  float* part = (float*)ws;
+  hipLaunchKernelGGL((bda_bwd_slab_kernel<T>), dim3(nslab, nsplit), dim3(256), 0, st, P, (const T*)dout, (T*)dx, part, rps);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(bda_bwd_finish_kernel, dim3((unsigned)((P.h + 255) / 256)), dim3(256), 0, st, (const float*)part, nsplit, P.h, dbias);
+  return hipGetLastError();
+}
+
+hipError_t launch_bias_dropout_add_bwd(const RowsParams& P, bool bf16, const void* dout, void* dx, float* dbias, void* ws, hipStream_t st) {
+  return bf16 ? bda_bwd_t<uint16_t>(P, dout, dx, dbias, ws, st) : bda_bwd_t<float>(P, dout, dx, dbias, ws, st);
 }
 
 }  // namespace sar

@@ -253,4 +253,38 @@ sar_status bias_dropout_add(const sar_rows_desc* desc, const void* x, const void
   return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_dropout_add launch");
 }
 
+sar_status bias_dropout_add_ln_fwd(const sar_rows_desc* desc, const void* x, const void* bias, const void* resid, const void* gamma, const void* beta,
+                                   void* out, void* y, float* mean, float* rstd, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!x || !resid || !gamma || !beta || !out || !y || !mean || !rstd) return fail(SAR_ERR_NULL, "bias_dropout_add_ln_fwd: NULL tensor pointer");
+  if (!aligned16(x) || !aligned16(resid) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out) || !aligned16(y) || (bias && !aligned16(bias)))
+    return fail(SAR_ERR_ALIGN, "bias_dropout_add_ln_fwd: pointer not 16-byte aligned");
+  if (out == x || y == x || y == resid || y == out) return fail(SAR_ERR_SHAPE, "bias_dropout_add_ln_fwd: out may alias resid only; y aliases nothing");
+  hipError_t e = sar::launch_bias_dropout_add_ln_fwd(P, desc->dtype == SAR_BF16, x, bias, resid, gamma, beta, out, y, mean, rstd, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_dropout_add_ln_fwd launch");
+}
+
+size_t bias_dropout_add_bwd_workspace(const sar_rows_desc* desc) {
+  if (check_rows_desc(desc, nullptr) != SAR_OK) return 0;
+  return sar::bda_bwd_workspace_bytes(desc->rows, desc->h);
+}
+
+sar_status bias_dropout_add_bwd(const sar_rows_desc* desc, const void* dout, void* dx, float* dbias, void* workspace, size_t workspace_bytes,
+                                void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!dout || !dx) return fail(SAR_ERR_NULL, "bias_dropout_add_bwd: NULL tensor pointer");
+  if (!aligned16(dout) || !aligned16(dx)) return fail(SAR_ERR_ALIGN, "bias_dropout_add_bwd: pointer not 16-byte aligned");
+  if (dbias) {
+    const size_t need = sar::bda_bwd_workspace_bytes(P.rows, P.h);
+    if (need && (!workspace || workspace_bytes < need)) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
+    if (need && !aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
+  }
+  hipError_t e = sar::launch_bias_dropout_add_bwd(P, desc->dtype == SAR_BF16, dout, dx, dbias, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_dropout_add_bwd launch");
+}
+
 }  // extern "C"

@@ -33,10 +33,12 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const float* p) { return *p; }
   static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+  static __device__ __forceinline__ float round(float v) { return v; }  // the value as it would be stored
 };
 template <> struct Elem<uint16_t> {  // bf16 bit pattern
   static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
   static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+  static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
 };
 
 // ---- Philox4x32-10 (Salmon et al., SC'11); the four output words for counter (g_lo, g_hi, 0, site) ----

@@ -52,5 +52,9 @@ hipError_t launch_ln_bwd(const RowsParams& P, bool bf16, const void* dy, const v
                          const void* gamma, void* dx, float* dgamma, float* dbeta, void* ws, hipStream_t st);
 hipError_t launch_bias_dropout_add(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, void* out,
                                    uint8_t* mask, hipStream_t st);
+hipError_t launch_bias_dropout_add_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* bias, const void* resid, const void* gamma,
+                                          const void* beta, void* out, void* y, float* mean, float* rstd, hipStream_t st);
+size_t bda_bwd_workspace_bytes(int64_t rows, int64_t h);
+hipError_t launch_bias_dropout_add_bwd(const RowsParams& P, bool bf16, const void* dout, void* dx, float* dbias, void* ws, hipStream_t st);
 
 }  // namespace sar

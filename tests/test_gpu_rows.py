@@ -95,3 +95,75 @@ def test_bias_dropout_add(rows, h, dtype, p):
     ref2 = oracle.bias_dropout_add(inp["x"], None, inp["resid"], p, seed, offset, row_offset)
     out2, _ = _run_bda(rows, h, dtype, inp, p, seed, offset, row_offset, bias=False, mask=False, inplace=True)
     assert err(out2, ref2["out"], dtype) <= BAR[dtype]
+
+
+@pytest.mark.parametrize("rows,h,dtype,p,bias", [
+    (128, 128, "f32", 0.1, True), (37, 1032, "bf16", 0.25, True), (9, 8, "bf16", 0.0, False), (3, 32768, "bf16", 0.1, True),
+    (1024, 6144, "bf16", 0.1, True), (256, 20480, "bf16", 0.1, True), (256, 25600, "bf16", 0.1, False),
+])
+def test_bias_dropout_add_ln_fwd(rows, h, dtype, p, bias):
+    """The fused step equals the composition of the two definitions: out as bias_dropout_add, y = LayerNorm(out)."""
+    from gpu_util import BAR, DT, dev, err, host
+    inp = rows_inputs(rows, h, dtype, seed=77)
+    seed, offset, row_offset = 4321, 12345, 3 * rows
+    print(f"bda+ln rows={rows} h={h} {dtype} p={p} bias={bias}", flush=True)
+    ref_o = oracle.bias_dropout_add(inp["x"], inp["bias"] if bias else None, inp["resid"], p, seed, offset, row_offset)
+    ref_l = oracle.ln_fwd(ref_o["out"], inp["gamma"], inp["beta"], 1e-5)
+    tdt, code = DT[dtype]
+    desc = sar.RowsDesc.make(rows, h, dtype=code, p=p, seed=seed, offset=offset, row_offset=row_offset)
+    x, resid, gamma, beta = (dev(inp[k], dtype) for k in ("x", "resid", "gamma", "beta"))
+    b = dev(inp["bias"], dtype) if bias else None
+    out, y = torch.empty_like(x), torch.empty_like(x)
+    mean = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty_like(mean)
+    sar.bias_dropout_add_ln_fwd(desc, x, b, resid, gamma, beta, out, y, mean, rstd)
+    torch.cuda.synchronize()
+    assert err(host(out), ref_o["out"], dtype) <= BAR[dtype]
+    # y and the statistics belong to the row as stored (rounded to the dtype): the definition applied to exactly
+    # those values is the reference at the usual bar ...
+    ref_s = oracle.ln_fwd(host(out), inp["gamma"], inp["beta"], 1e-5)
+    assert err(host(y), ref_s["y"], dtype) <= BAR[dtype]
+    assert err(host(mean), ref_s["mean"], "f32") <= 1e-4
+    assert err(host(rstd), ref_s["rstd"], "f32") <= 1e-4
+    # ... and against the unrounded fp64 composition y carries two roundings (of out, then of y)
+    assert err(host(y), ref_l["y"], dtype) <= 2 * BAR[dtype]
+    # the unfused entry points give the same bits for `out`
+    out2 = torch.empty_like(x)
+    sar.bias_dropout_add(desc, x, b, resid, out2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # in-place residual
+    sar.bias_dropout_add_ln_fwd(desc, x, b, resid, gamma, beta, resid, y, mean, rstd)
+    torch.cuda.synchronize()
+    assert torch.equal(resid, out2)
+
+
+@pytest.mark.parametrize("rows,h,dtype,p", [
+    (128, 128, "f32", 0.1), (37, 1032, "bf16", 0.25), (9, 8, "bf16", 0.0), (1000, 64, "f32", 0.5),
+    (1024, 6144, "bf16", 0.1), (256, 20480, "bf16", 0.1), (256, 25600, "bf16", 0.1),
+])
+def test_bias_dropout_add_bwd(rows, h, dtype, p):
+    from gpu_util import BAR, DT, dev, err, host
+    inp = rows_inputs(rows, h, dtype, seed=55)
+    seed, offset, row_offset = 1234, (1 << 32) - 3, 7 * rows
+    print(f"bda bwd rows={rows} h={h} {dtype} p={p}", flush=True)
+    ref = oracle.bias_dropout_add_bwd(inp["dy"], p, seed, offset, row_offset)
+    tdt, code = DT[dtype]
+    desc = sar.RowsDesc.make(rows, h, dtype=code, p=p, seed=seed, offset=offset, row_offset=row_offset)
+    dout = dev(inp["dy"], dtype)
+    dx = torch.empty_like(dout)
+    dbias = torch.empty(h, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, sar.bias_dropout_add_bwd_workspace(desc)), dtype=torch.uint8, device="cuda")
+    sar.bias_dropout_add_bwd(desc, dout, dx, dbias, ws)
+    torch.cuda.synchronize()
+    assert err(host(dx), ref["dx"], dtype) <= BAR[dtype]
+    # dbias sums the unrounded fp32 products in fp32
+    assert err(host(dbias), ref["dbias"], "f32") <= 1e-4
+    # dropped positions are exactly zero and agree with the forward's mask
+    m = oracle.bias_dropout_add(inp["x"], None, inp["resid"], p, seed, offset, row_offset)["mask"]
+    assert np.array_equal(host(dx) != 0, (m != 0) & (np.asarray(inp["dy"], dtype=np.float64) != 0))
+    # without dbias: elementwise kernel, same dx bits, no workspace
+    dx2 = torch.empty_like(dout)
+    sar.bias_dropout_add_bwd(desc, dout, dx2, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx2)
