@@ -54,7 +54,7 @@ def main():
         return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).cuda()
 
     q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=w.seed)
-    desc = sar.AttnDesc.packed(s, b, w.a, w.h, t=w.t, rank=0, dtype=SAR_BF16, p=w.p, seed=w.seed)
+    desc = sar.AttnDesc.packed(s, b, w.a, w.h, t=w.t, rank=0, dtype=SAR_BF16, p=w.p, seed=w.seed, causal=w.causal)
     tq, tk, tv, tdo = (dev(x) for x in (q, k, v, do))
     o, dq, dk, dv = (torch.empty_like(tq) for _ in range(4))
     lse = torch.empty((b, A, s), dtype=torch.float32, device="cuda")
@@ -111,8 +111,8 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kern_ms = {n: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps)])) for j, n in enumerate(names)}
 
-    # algorithmic work (causal pairs T = s(s+1)/2 per head)
-    T = s * (s + 1) // 2
+    # algorithmic work (causal: T = s(s+1)/2 score pairs per head; every key: s^2)
+    T = s * (s + 1) // 2 if w.causal else s * s
     one = 2 * d * T * N
     flops = {"attn_core_fwd": 2 * one, "attn_bwd_dq": 3 * one, "attn_bwd_dkdv": 4 * one}   # executed contractions
     flops_alg_fwd_bwd = 14 * d * T * N                                                      # 2 fwd + 5 bwd contractions
@@ -184,7 +184,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
-        sh = oracle.AttnShape(s=s, b=b, a=w.a, h=w.h, t=w.t, rank=0, p=w.p, seed=w.seed)
+        sh = oracle.AttnShape(s=s, b=b, a=w.a, h=w.h, t=w.t, rank=0, p=w.p, seed=w.seed, causal=w.causal)
         nthreads = oracle.num_threads()
         nh = min(N, max(1, nthreads))
         c0 = time.perf_counter()
@@ -203,7 +203,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}-class per-GPU shard: attention core b={b} s={s} heads={A} head_dim={d} causal p={w.p}; "
+        "config": {"workload": f"{args.workload}-class per-GPU shard: attention core b={b} s={s} heads={A} head_dim={d} {'causal' if w.causal else 'no mask'} p={w.p}; "
                                f"LayerNorm fwd/bwd + bias-dropout-add on {rows}x{h} bf16", "t": w.t},
         "pct_mfma_peak": 100.0 * value / PEAK_BF16_MFMA_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",

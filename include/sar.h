@@ -60,7 +60,7 @@ typedef struct {
                               local head n has global index rank*(a/t) + n (used by Philox only)  */
   int32_t h;               /* hidden size; head dimension d = h / a                                */
   int32_t dtype;           /* sar_dtype of Q, K, V, O, dO, dQ, dK, dV                              */
-  int32_t causal;          /* must be 1 (decoder mask, keys j <= i)                                */
+  int32_t causal;          /* 1: decoder mask, keys j <= i (Section 6's models); 0: every key      */
   float scale;             /* alpha applied to QK^T; pass 1/sqrt(d)                                */
   float p;                 /* softmax-dropout probability, 0 <= p < 1                              */
   uint64_t seed, offset;   /* Philox key and counter base                                          */

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
   const int jw0 = kb * BN + kgp * 32;  // first key of this wave
 
   const int nit = (P.s + BI - 1) / BI;
-  const int it0 = kb;  // BI == BN: the first tile with rows >= this block's keys
+  const int it0 = P.causal ? kb : 0;  // BI == BN: the first tile with rows that attend to this block's keys
   const uint16_t* qg = q + base;
   const uint16_t* dog = dO + base;
   DmaMap<D> map;
@@ -45,12 +45,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
     dma_tile<D>(map, k + base + (int64_t)(kb * BN) * gstride, Ksm, wave);
     dma_tile<D>(map, v + base + (int64_t)(kb * BN) * gstride, Vsm, wave);
     map.init(wave, lane, gstride, false);
-    if (left >= BI) {
+    const int leftq = P.s - it0 * BI;  // rows left from the first query tile
+    if (leftq >= BI) {
       dma_tile<D>(map, qg + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE, wave);
       dma_tile<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave);
     } else {
-      dma_tile_ragged<D>(map, qg + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE, wave, lane, gstride, left);
-      dma_tile_ragged<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave, lane, gstride, left);
+      dma_tile_ragged<D>(map, qg + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE, wave, lane, gstride, leftq);
+      dma_tile_ragged<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave, lane, gstride, leftq);
     }
   }
   if (tid < BI) {
@@ -115,8 +116,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
     const float* lse_c = lse_s[it & 1];
     const float* delta_c = delta_s[it & 1];
     const int i0w = i0 + 32 * is;  // this wave's 32 rows
-    if (i0w + 31 >= jw0) {         // otherwise every row precedes this wave's keys
-      const bool diag = (i0w < jw0 + 31);
+    if (!P.causal || i0w + 31 >= jw0) {  // otherwise every row precedes this wave's keys
+      const bool diag = P.causal && (i0w < jw0 + 31);
       float16_t st, dd;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (i >= P.s || jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+          if (i >= P.s || (P.causal && jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i)) st[e] = -INFINITY;
       }
       bf16x8_t df[2], dsf[2];
 #pragma unroll

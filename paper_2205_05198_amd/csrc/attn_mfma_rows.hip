@@ -58,6 +58,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   const int iw0 = rb * BM + rg * 32;  // first row of this wave
   const int i = iw0 + li;
   const int i_ld = i < P.s ? i : P.s - 1;
+  const int jlim = P.causal ? i : P.s - 1;  // last key row i attends to
 
   bf16x8_t qf[KC];
 #pragma unroll
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   const float sc2 = P.scale * kLog2e;
 
   const int last_row = min(rb * BM + BM - 1, P.s - 1);
-  const int ntile = last_row / BN + 1;  // the last tile is the one on the diagonal
+  const int ntile = P.causal ? last_row / BN + 1 : (P.s + BN - 1) / BN;  // the last tile is the only one that needs a mask
   DmaMap<D> map;
   map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
     else dma_tile_ragged<D>(map, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, wave, lane, gstride, left);
   };
   // S^T tile of this wave's 32 keys of tile jt against its 32 rows; st[8*c + e] is the score of key
-  // jt*64 + 32*ks + 16*c + 8*hh + e.  DIAG: the tile touches the diagonal, keys j > i are masked.
+  // jt*64 + 32*ks + 16*c + 8*hh + e.  DIAG: the last tile of the row block: keys beyond jlim (above the diagonal, or past the end) are masked.
   auto scores = [&](const int jt, auto diag) __attribute__((always_inline)) {
     const uint16_t* Ks = Kst + (jt & 1) * TILE;
     float16_t st;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
       const int j0w = jt * BN + 32 * ks;
 #pragma unroll
       for (int e = 0; e < 16; ++e)
-        if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+        if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > jlim) st[e] = -INFINITY;
     }
     return st;
   };
@@ -235,6 +236,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
   const int iw0 = rb * BM + rg * 32;
   const int i = iw0 + li;
   const int i_ld = i < P.s ? i : P.s - 1;
+  const int jlim = P.causal ? i : P.s - 1;                     // last key row i attends to
+  const int lim_lo = P.causal ? iw0 : P.s - 1, lim_hi = P.causal ? iw0 + 31 : P.s - 1;  // its range over the wave's rows
 
   bf16x8_t qf[KC], dof[KC];
   float dpart = 0.f;
@@ -262,7 +265,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
     for (int e = 0; e < 16; ++e) dqacc[dt][e] = 0.f;
 
   const int last_row = min(rb * BM + BM - 1, P.s - 1);
-  const int ntile = last_row / BN + 1;
+  const int ntile = P.causal ? last_row / BN + 1 : (P.s + BN - 1) / BN;
   DmaMap<D> map;
   map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
@@ -297,8 +300,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
       dma_tile<D>(map, vn, nxt + TILE, wave);
     }
     const int j0w = j0 + 32 * ks;
-    if (j0w <= iw0 + 31) {
-      const bool diag = (j0w + 31 > iw0);
+    if (j0w <= lim_hi) {
+      const bool diag = (j0w + 31 > lim_lo);  // some of the wave's keys are masked for some of its rows
       float16_t st, dd;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
         asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+          if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > jlim) st[e] = -INFINITY;
       }
       if (MODE == 1 && wave == 1) {  // pinned after the score tile
         float tok = st[0];

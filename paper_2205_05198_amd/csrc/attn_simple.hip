@@ -30,11 +30,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_fwd_simple_kernel(At
   float* qrow = prow + P.s;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int ic = valid ? i : 0;
+  const int jend = P.causal ? i : P.s - 1;  // last key this row attends to
   for (int x = lane; x < P.d; x += 64) qrow[x] = Elem<T>::load(q + base + (int64_t)ic * P.stride_s + x);
   __syncthreads();
   float mx = -INFINITY;
   if (valid)
-    for (int j = lane; j <= i; j += 64) {
+    for (int j = lane; j <= jend; j += 64) {
       const T* kj = k + base + (int64_t)j * P.stride_s;
       float acc = 0.f;
       for (int x = 0; x < P.d; ++x) acc = fmaf(qrow[x], Elem<T>::load(kj + x), acc);
@@ -45,7 +46,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_fwd_simple_kernel(At
   mx = wave_max(mx);
   float sum = 0.f;
   if (valid)
-    for (int j = lane; j <= i; j += 64) {
+    for (int j = lane; j <= jend; j += 64) {
       float e = expf(prow[j] - mx);
       prow[j] = e;
       sum += e;
@@ -55,7 +56,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_fwd_simple_kernel(At
   if (valid) {
     const size_t srow = ((size_t)bn * P.s + i) * P.s;
     for (int j = lane; j < P.s; j += 64) {
-      if (j <= i) {
+      if (j <= jend) {
         float pj = prow[j] * inv;
         uint32_t keep = keep_bit1(score_elem(P, beta, n, i, j), P.offset, 0u, P.key0, P.key1, P.thresh);
         float dj = keep ? pj * P.keep_scale : 0.f;
@@ -77,7 +78,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_fwd_simple_kernel(At
   if (valid) {
     for (int x = lane; x < P.d; x += 64) {
       float acc = 0.f;
-      for (int j = 0; j <= i; ++j) acc = fmaf(prow[j], Elem<T>::load(v + base + (int64_t)j * P.stride_s + x), acc);
+      for (int j = 0; j <= jend; ++j) acc = fmaf(prow[j], Elem<T>::load(v + base + (int64_t)j * P.stride_s + x), acc);
       Elem<T>::store(o + base + (int64_t)i * P.stride_s + x, acc);
     }
     if (lane == 0 && lse) lse[(size_t)bn * P.s + i] = mx + logf(sum);
@@ -106,6 +107,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_bwd_rows_simple_kern
   float* dorow = qrow + kMaxD;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int ic = valid ? i : 0;
+  const int jend = P.causal ? i : P.s - 1;  // last key this row attends to
   float dsum = 0.f;
   for (int x = lane; x < P.d; x += 64) {
     qrow[x] = Elem<T>::load(q + base + (int64_t)ic * P.stride_s + x);
@@ -117,7 +119,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_bwd_rows_simple_kern
   const size_t srow = ((size_t)bn * P.s + ic) * P.s;
   float psum = 0.f;
   if (valid)
-    for (int j = lane; j <= i; j += 64) {
+    for (int j = lane; j <= jend; j += 64) {
       const T* kj = k + base + (int64_t)j * P.stride_s;
       const T* vj = v + base + (int64_t)j * P.stride_s;
       float accd = 0.f;
@@ -140,20 +142,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_bwd_rows_simple_kern
     }
   const float dl = STORED ? wave_sum(psum) : wave_sum(dsum);
   if (valid) {
-    for (int j = lane; j <= i; j += 64) dsrow[j] = prow[j] * (dsrow[j] - dl);
+    for (int j = lane; j <= jend; j += 64) dsrow[j] = prow[j] * (dsrow[j] - dl);
     if (lane == 0) delta[(size_t)bn * P.s + i] = dl;
   }
   __syncthreads();
   if (valid)
     for (int x = lane; x < P.d; x += 64) {
       float acc = 0.f;
-      for (int j = 0; j <= i; ++j) acc = fmaf(dsrow[j], Elem<T>::load(k + base + (int64_t)j * P.stride_s + x), acc);
+      for (int j = 0; j <= jend; ++j) acc = fmaf(dsrow[j], Elem<T>::load(k + base + (int64_t)j * P.stride_s + x), acc);
       Elem<T>::store(dq + base + (int64_t)i * P.stride_s + x, P.scale * acc);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------
-// backward, column pass: dK_j = alpha sum_i dS_ij q_i, dV_j = sum_i D_ij dO_i, i >= j.
+// backward, column pass: dK_j = alpha sum_i dS_ij q_i, dV_j = sum_i D_ij dO_i, over the rows i that attend to key j.
 // ---------------------------------------------------------------------------------------------------
 template <typename T, bool STORED>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_bwd_cols_simple_kernel(AttnParams P, const T* __restrict__ q, const T* __restrict__ k,
@@ -176,11 +178,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_bwd_cols_simple_kern
   __syncthreads();
   float acck[kMaxD / 64] = {0.f, 0.f, 0.f, 0.f}, accv[kMaxD / 64] = {0.f, 0.f, 0.f, 0.f};
   // every wave of the block runs the same number of chunk iterations so that the barriers match
-  const int j_first = blockIdx.x * kWavesPerBlock;
+  const int j_first = P.causal ? blockIdx.x * kWavesPerBlock : 0;
   for (int i0 = j_first; i0 < P.s; i0 += 64) {
     const int i = i0 + lane;
     float ds = 0.f, dd = 0.f;
-    if (valid && i >= j && i < P.s) {
+    if (valid && (i >= j || !P.causal) && i < P.s) {
       const T* doi = dO + base + (int64_t)i * P.stride_s;
       float accd = 0.f;
       for (int x = 0; x < P.d; ++x) accd = fmaf(Elem<T>::load(doi + x), sv[wave][x], accd);

@@ -32,7 +32,7 @@ sar_status check_attn_desc(const sar_attn_desc* c, sar::AttnParams* P) {
   if (c->h % c->a != 0) return fail(SAR_ERR_SHAPE, "h (%d) is not a multiple of a (%d)", c->h, c->a);
   if (c->rank < 0 || c->rank >= c->t) return fail(SAR_ERR_SHAPE, "rank %d outside [0, t)", c->rank);
   if (c->dtype != SAR_F32 && c->dtype != SAR_BF16) return fail(SAR_ERR_UNSUPPORTED, "dtype %d", c->dtype);
-  if (c->causal != 1) return fail(SAR_ERR_UNSUPPORTED, "only the causal core is built (causal = %d)", c->causal);
+  if (c->causal != 0 && c->causal != 1) return fail(SAR_ERR_SHAPE, "causal must be 0 or 1 (got %d)", c->causal);
   if (!(c->p >= 0.f && c->p < 1.f)) return fail(SAR_ERR_PROB, "dropout probability %g outside [0, 1)", (double)c->p);
   if (!std::isfinite(c->scale)) return fail(SAR_ERR_SHAPE, "scale is not finite");
   const int d = c->h / c->a, A = c->a / c->t;
@@ -48,6 +48,7 @@ sar_status check_attn_desc(const sar_attn_desc* c, sar::AttnParams* P) {
     P->s = c->s; P->b = c->b; P->A = A; P->d = d;
     P->a_global = c->a; P->head0 = c->rank * A;
     P->stride_s = c->stride_s; P->stride_b = c->stride_b; P->stride_a = c->stride_a;
+    P->causal = c->causal;
     P->scale = c->scale; P->p = c->p; P->keep_scale = 1.0f / (1.0f - c->p);
     P->thresh = dropout_threshold(c->p);
     P->key0 = (uint32_t)(c->seed & 0xFFFFFFFFu); P->key1 = (uint32_t)(c->seed >> 32);

@@ -9,6 +9,7 @@ namespace sar {
 
 struct AttnParams {
   int s, b, A, d;               // per-GPU share: A = a/t local heads, d = h/a
+  int causal;                   // 1: keys j <= i only (decoder); 0: every key (encoder)
   int a_global, head0;          // global head count and global index of local head 0 (Philox indexing)
   int64_t stride_s, stride_b, stride_a;
   float scale;                  // alpha

@@ -24,6 +24,7 @@ class Workload:
     seed: int       # Philox seed
     rows: int       # rows of the sequence-parallel shard, (s/t)*b
     rows_h: int     # width of the LayerNorm / dropout-add rows
+    causal: int = 1  # 1: decoder mask (the paper's models); 0: every key
 
     @property
     def A(self) -> int:
@@ -42,6 +43,11 @@ WORKLOADS = {
     "175B": Workload("175B", "bf16", 2048, 1, 96, 12288, 8, 0.1, 1234, 256, 12288),
     "530B": Workload("530B", "bf16", 2048, 1, 128, 20480, 8, 0.1, 1234, 256, 20480),
     "1T": Workload("1T", "bf16", 2048, 1, 160, 25600, 8, 0.1, 1234, 256, 25600),
+    # variants of the 530B shard: longer sequences (activation memory of the selective core grows linearly in s,
+    # Eq. 6) and the encoder form of the core (no causal mask)
+    "530B_s4096": Workload("530B_s4096", "bf16", 4096, 1, 128, 20480, 8, 0.1, 1234, 512, 20480),
+    "530B_s8192": Workload("530B_s8192", "bf16", 8192, 1, 128, 20480, 8, 0.1, 1234, 1024, 20480),
+    "530B_enc": Workload("530B_enc", "bf16", 2048, 1, 128, 20480, 8, 0.1, 1234, 256, 20480, 0),
 }
 
 

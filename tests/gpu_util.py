@@ -72,7 +72,7 @@ def run_attn(sh, dtype, q, k, v, do, stored=False):
     sh: oracle.AttnShape (used only for its numbers)."""
     tdt, code = DT[dtype]
     desc = sar.AttnDesc.packed(sh.s, sh.b, sh.a, sh.h, t=sh.t, rank=sh.rank, dtype=code, p=sh.p, seed=sh.seed, offset=sh.offset,
-                               scale=sh.alpha())
+                               scale=sh.alpha(), causal=sh.causal)
     dq_, dk_, dv_, dd = (dev(x, dtype) for x in (q, k, v, do))
     o = torch.empty_like(dq_)
     gq, gk, gv = (torch.empty_like(dq_) for _ in range(3))

@@ -73,7 +73,7 @@ def test_attention_argument_errors(lib):
     assert fwd(d) == -2
     assert fwd(sar.AttnDesc.packed(s=100, b=1, a=2, h=128)) == -3                   # s % 8
     assert fwd(sar.AttnDesc.packed(s=128, b=1, a=2, h=2 * 260)) == -3               # d > 256
-    assert fwd(sar.AttnDesc.packed(**good, causal=0)) == -3
+    assert fwd(sar.AttnDesc.packed(**good, causal=2)) == -2                         # 0 (every key) and 1 (decoder mask) only
     assert fwd(sar.AttnDesc.packed(**good, dtype=7)) == -3
     assert fwd(sar.AttnDesc.packed(**good, p=1.0)) == -5
     assert fwd(sar.AttnDesc.packed(**good, p=-0.1)) == -5

@@ -65,10 +65,13 @@ def test_tiny_fp32_workload():
     (136, 1, 4, 2, 1, 64, 0.1, 4.0, True),     # peaked softmax, late-moving maximum, second TP rank
     (64, 1, 1, 1, 0, 8, 0.0, 1.0, False),      # p = 0, smallest head dimension
     (8, 1, 2, 1, 0, 256, 0.5, 1.0, False),     # one block, largest head dimension
+    (-104, 1, 2, 1, 0, 64, 0.1, 1.0, False),   # negative s: the same without the causal mask (encoder), ragged
+    (-40, 2, 3, 1, 0, 32, 0.0, 4.0, True),
 ])
 def test_fp32_shapes(s, b, a, t, rank, d, p, std, outlier):
     from gpu_util import run_attn
-    sh = oracle.AttnShape(s=s, b=b, a=a, h=a * d, t=t, rank=rank, p=p, seed=77, offset=123456789012)
+    causal, s = int(s > 0), abs(s)
+    sh = oracle.AttnShape(s=s, b=b, a=a, h=a * d, t=t, rank=rank, p=p, seed=77, offset=123456789012, causal=causal)
     q, k, v, do = attn_inputs(s, b, sh.A, d, "f32", seed=5, qk_std=std, outlier=outlier)
     print(f"fp32 s={s} b={b} A={sh.A} d={d} p={p}", flush=True)
     got = run_attn(sh, "f32", q, k, v, do)
@@ -78,11 +81,12 @@ def test_fp32_shapes(s, b, a, t, rank, d, p, std, outlier):
 
 
 @pytest.mark.parametrize("d", [64, 96, 128, 160])
-@pytest.mark.parametrize("s,b,A,p,std", [(200, 2, 2, 0.1, None), (328, 1, 3, 0.25, 1.0)])
-def test_bf16_matrix_core_path_small(d, s, b, A, p, std):
-    """Several 64-key tiles and 64-row blocks plus a ragged tail (s % 64 = 8), every benchmark head dimension."""
+@pytest.mark.parametrize("s,b,A,p,std,causal", [(200, 2, 2, 0.1, None, 1), (328, 1, 3, 0.25, 1.0, 1), (200, 1, 2, 0.1, None, 0), (264, 1, 1, 0.0, 1.0, 0)])
+def test_bf16_matrix_core_path_small(d, s, b, A, p, std, causal):
+    """Several 64-key tiles and 64-row blocks plus a ragged tail (s % 64 = 8), every benchmark head dimension;
+    causal = 0 is the encoder variant (every key), including p = 0."""
     from gpu_util import run_attn
-    sh = oracle.AttnShape(s=s, b=b, a=A * 2, h=A * 2 * d, t=2, rank=1, p=p, seed=1234, offset=(1 << 33) + 5)
+    sh = oracle.AttnShape(s=s, b=b, a=A * 2, h=A * 2 * d, t=2, rank=1, p=p, seed=1234, offset=(1 << 33) + 5, causal=causal)
     q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=9, qk_std=std, outlier=std is not None)
     print(f"bf16 s={s} b={b} A={A} d={d} p={p} std={std}", flush=True)
     got = run_attn(sh, "bf16", q, k, v, do)
@@ -97,17 +101,17 @@ def test_bf16_generic_path_other_head_dim():
     _check_bf16_heads("bf16-d40", sh, q, k, v, do, got, range(2))
 
 
-@pytest.mark.parametrize("dtype,d", [("f32", 64), ("bf16", 96)])
-def test_stored_baseline_mask_bit_exact(dtype, d):
-    """The stored path exposes P, M, D: M must equal the oracle's mask bit for bit (0 above the diagonal)."""
+@pytest.mark.parametrize("dtype,d,causal", [("f32", 64, 1), ("bf16", 96, 1), ("bf16", 96, 0)])
+def test_stored_baseline_mask_bit_exact(dtype, d, causal):
+    """The stored path exposes P, M, D: M must equal the oracle's mask bit for bit (0 above the diagonal when causal)."""
     from gpu_util import BAR, err, run_attn
-    sh = oracle.AttnShape(s=128, b=2, a=4, h=4 * d, t=2, rank=1, p=0.1, seed=1234, offset=77)
+    sh = oracle.AttnShape(s=128, b=2, a=4, h=4 * d, t=2, rank=1, p=0.1, seed=1234, offset=77, causal=causal)
     q, k, v, do = attn_inputs(128, 2, 2, d, dtype, seed=31)
     got = run_attn(sh, dtype, q, k, v, do, stored=True)
     f = oracle.attn_fwd(sh, q, k, v, materialise=True)
     g = oracle.attn_bwd(sh, q, k, v, do)
     assert np.array_equal(got["M"], f["M"])
-    assert np.array_equal(got["M"], np.tril(oracle.attn_mask(sh)))
+    assert np.array_equal(got["M"], np.tril(oracle.attn_mask(sh)) if causal else oracle.attn_mask(sh))
     for nm in ("P", "D"):
         assert np.max(np.abs(got[nm] - f[nm])) <= (1e-6 if dtype == "f32" else 2.0 ** -8), nm
     if dtype == "f32":
@@ -146,3 +150,14 @@ def test_full_size_sampled_heads(name, heads):
     got = run_attn(sh, "bf16", q, k, v, do)
     _check_bf16_heads(name, sh, q, k, v, do, got, heads)
     sys.stdout.flush()
+
+
+def test_longer_sequence_single_head():
+    """s = 4096 at the 530B head dimension (64 tiles per row block): one head against the oracle."""
+    from gpu_util import run_attn
+    s, d = 4096, 160
+    sh = oracle.AttnShape(s=s, b=1, a=8, h=8 * d, t=8, rank=5, p=0.1, seed=1234, offset=99)
+    q, k, v, do = attn_inputs(s, 1, 1, d, "bf16", seed=61)
+    print("bf16 s=4096 one head", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    _check_bf16_heads("s4096", sh, q, k, v, do, got, range(1))

@@ -76,6 +76,23 @@ def test_noncausal_matches_library():
     assert np.abs(oracle.attn_fwd(sh, q, k, v)["o"] - _from_bhsd(ref)).max() < 1e-13
 
 
+def test_noncausal_backward_matches_autograd_and_mask_is_full():
+    """Encoder variant: every key; gradients against autograd at p = 0, and with dropout every (i, j) draws a bit."""
+    sh = oracle.AttnShape(s=24, b=1, a=2, h=2 * 12, p=0.0, causal=0)
+    q, k, v, do = (_rand((sh.s, sh.b, sh.A, sh.d), 70 + i) for i in range(4))
+    tq, tk, tv = (_to_bhsd(x).requires_grad_(True) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=False, scale=sh.alpha())
+    ref.backward(_to_bhsd(do))
+    g = oracle.attn_bwd(sh, q, k, v, do)
+    for name, t in (("dq", tq), ("dk", tk), ("dv", tv)):
+        assert np.abs(g[name] - _from_bhsd(t.grad)).max() < 1e-12, name
+    shd = oracle.AttnShape(s=24, b=1, a=2, h=2 * 12, p=0.4, seed=11, causal=0)
+    f = oracle.attn_fwd(shd, q, k, v, materialise=True)
+    assert np.array_equal(f["M"], oracle.attn_mask(shd))           # nothing is cut away above the diagonal
+    assert np.allclose(f["P"].sum(-1), 1.0) and (f["P"] > 0).all()  # full rows
+    assert np.allclose(f["D"], f["P"] * f["M"] / (1.0 - float(np.float32(0.4))))
+
+
 def test_backward_finite_differences_with_dropout():
     sh = oracle.AttnShape(s=8, b=1, a=2, h=8, p=0.25, seed=3, offset=17)
     q, k, v, do = (_rand((sh.s, sh.b, sh.A, sh.d), 40 + i) for i in range(4))
