@@ -12,7 +12,8 @@ namespace sar {
 // P, D, dS are produced with one query row per lane; the two products above contract over i, so the bf16
 // tiles are first moved to the one-key-per-lane layout by multiplying with an identity on the matrix core.
 // ===================================================================================================
-template <int D>
+// DROP = false is the p = 0 variant: no random numbers are drawn at all.
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v, const float* __restrict__ lse,
                                                                 const uint16_t* __restrict__ dO, const float* __restrict__ delta,
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int jc = jw0 + 16 * c + 8 * hh;
-        const uint32_t keep = keep_bits8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1, P.thresh);
+        const uint32_t keep = DROP ? keep_bits8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1, P.thresh) : 0xFFu;
         float dvv[8], ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -223,8 +224,12 @@ template <int D>
 static hipError_t bwd_dkdv_d(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO, const float* delta,
                              void* dk, void* dv, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
-  hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
-                     (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+  if (P.thresh != 0)
+    hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D, true>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+  else
+    hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D, false>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
   return hipGetLastError();
 }
 

@@ -38,7 +38,8 @@ static constexpr float kLazyRescale = 60.0f;  // the running reference exponent 
 // causal mask only exists in the variants of the step that produce the diagonal tile, and the (rare) rescaling
 // of the running maximum for tile j+1 is decided at the end of step j.
 // ===================================================================================================
-template <int D>
+// DROP = false is the p = 0 variant: no random numbers are drawn at all.
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
   constexpr int BM = 64, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
@@ -142,13 +143,14 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
     bf16x8_t pf[2];
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
-      const Philox4 rnd = philox_call8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1);
+      Philox4 rnd = {0u, 0u, 0u, 0u};
+      if (DROP) rnd = philox_call8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1);
       float pd[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
         psum += pe;
-        pd[e] = keep_field(rnd, e, P.thresh) ? pe : 0.f;
+        pd[e] = (!DROP || keep_field(rnd, e, P.thresh)) ? pe : 0.f;
       }
       pf[c] = pack8(pd);
     }
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
 // P_ij = exp(alpha q_i.k_j - LSE_i), dP = (dO V^T) o M/(1-p), dS = P o (dP - delta) recomputed per tile.
 // Same workgroup shape as the forward.
 // ===================================================================================================
-template <int D>
+template <int D, bool DROP>
 __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                               const uint16_t* __restrict__ v, const uint16_t* __restrict__ o,
                                                               const float* __restrict__ lse, const uint16_t* __restrict__ dO,
@@ -326,17 +328,25 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int jc = j0w + 16 * c + 8 * hh;
-        Philox4 rnd = philox_call8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1);
+        Philox4 rnd = {0u, 0u, 0u, 0u};
+        if (DROP) rnd = philox_call8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1);
         // waves 2 and 3 issue their loads of the next tile after the first / second random-number block
         if (MODE == 1 && wave == 2 + c) {
-          dma_tile<D>(map, kn, nxt, wave, rnd.x);
-          dma_tile<D>(map, vn, nxt + TILE, wave, rnd.x);
+          if (DROP) {
+            dma_tile<D>(map, kn, nxt, wave, rnd.x);
+            dma_tile<D>(map, vn, nxt + TILE, wave, rnd.x);
+          } else {
+            float tok = st[8 * c];
+            dma_tile<D>(map, kn, nxt, wave, tok);
+            dma_tile<D>(map, vn, nxt + TILE, wave, tok);
+            st[8 * c] = tok;
+          }
         }
         float ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          const float dp = keep_field(rnd, e, P.thresh) ? dd[8 * c + e] * P.keep_scale : 0.f;
+          const float dp = (!DROP || keep_field(rnd, e, P.thresh)) ? dd[8 * c + e] * P.keep_scale : 0.f;
           ds[e] = pe * (dp - dl);
         }
         dsf[c] = pack8(ds);
@@ -382,8 +392,12 @@ bool attn_mfma_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 
 template <int D>
 static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const void* v, void* o, float* lse, hipStream_t st) {
   const int N = P.b * P.A, nrb = (P.s + 63) / 64;
-  hipLaunchKernelGGL((attn_fwd_mfma_kernel<D>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
-                     (const uint16_t*)v, (uint16_t*)o, lse);
+  if (P.thresh != 0)
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (uint16_t*)o, lse);
+  else  // every element is kept: the variant that draws no random numbers
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (uint16_t*)o, lse);
   return hipGetLastError();
 }
 
@@ -401,8 +415,12 @@ template <int D>
 static hipError_t bwd_dq_d(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
                            float* delta, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
-  hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
-                     (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);
+  if (P.thresh != 0)
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);
+  else
+    hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, false>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);
   return hipGetLastError();
 }
 

@@ -81,7 +81,8 @@ def test_fp32_shapes(s, b, a, t, rank, d, p, std, outlier):
 
 
 @pytest.mark.parametrize("d", [64, 96, 128, 160])
-@pytest.mark.parametrize("s,b,A,p,std,causal", [(200, 2, 2, 0.1, None, 1), (328, 1, 3, 0.25, 1.0, 1), (200, 1, 2, 0.1, None, 0), (264, 1, 1, 0.0, 1.0, 0)])
+@pytest.mark.parametrize("s,b,A,p,std,causal", [(200, 2, 2, 0.1, None, 1), (328, 1, 3, 0.25, 1.0, 1), (200, 1, 2, 0.1, None, 0), (264, 1, 1, 0.0, 1.0, 0),
+                                                 (200, 1, 2, 0.0, None, 1)])
 def test_bf16_matrix_core_path_small(d, s, b, A, p, std, causal):
     """Several 64-key tiles and 64-row blocks plus a ragged tail (s % 64 = 8), every benchmark head dimension;
     causal = 0 is the encoder variant (every key), including p = 0."""
