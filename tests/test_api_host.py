@@ -108,3 +108,29 @@ def test_rows_argument_errors(lib):
     assert lib.bias_dropout_add(ctypes.byref(sar.RowsDesc.make(16, 128, p=1.5)), *p[:5], st) == -5
     assert lib.bias_dropout_add(ctypes.byref(d), p[0], None, p[1], p[0], None, st) == -2  # out aliases x
     assert lib.bias_dropout_add(ctypes.byref(d), None, None, p[1], p[2], None, st) == -1
+
+
+def test_dropout_add_neighbours_argument_errors(lib):
+    """bias_dropout_add_ln_fwd and bias_dropout_add_bwd reject bad arguments before any launch."""
+    p = _fake(12)
+    st = ctypes.c_void_p(0)
+    d = sar.RowsDesc.make(16, 128, p=0.1)
+    # fused forward: (desc, x, bias, resid, gamma, beta, out, y, mean, rstd, stream)
+    assert lib.bias_dropout_add_ln_fwd(None, *p[:9], st) == -1
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(d), p[0], None, p[2], p[3], p[4], p[5], None, p[7], p[8], st) == -1   # y missing
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(d), p[0], None, p[2], p[3], p[4], p[0], p[6], p[7], p[8], st) == -2   # out aliases x
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(d), p[0], None, p[2], p[3], p[4], p[5], p[5], p[7], p[8], st) == -2   # y aliases out
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(d), p[0], ctypes.c_void_p(0x2004), p[2], p[3], p[4], p[5], p[6], p[7], p[8], st) == -4
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(sar.RowsDesc.make(16, 128, p=1.0)), *p[:9], st) == -5
+    assert lib.bias_dropout_add_ln_fwd(ctypes.byref(sar.RowsDesc.make(16, 100)), *p[:9], st) == -3
+    # backward: (desc, dout, dx, dbias, workspace, workspace_bytes, stream)
+    assert lib.bias_dropout_add_bwd(None, p[0], p[1], None, None, 0, st) == -1
+    assert lib.bias_dropout_add_bwd(ctypes.byref(d), None, p[1], None, None, 0, st) == -1
+    assert lib.bias_dropout_add_bwd(ctypes.byref(d), ctypes.c_void_p(0x1008), p[1], None, None, 0, st) == -4
+    tall = sar.RowsDesc.make(4096, 64, p=0.1)     # one column slab, many rows: the rows are split and partial sums need scratch
+    need = lib.bias_dropout_add_bwd_workspace(ctypes.byref(tall))
+    assert need >= 2 * 64 * 4
+    assert lib.bias_dropout_add_bwd(ctypes.byref(tall), p[0], p[1], p[2], None, 0, st) == -6
+    assert lib.bias_dropout_add_bwd(ctypes.byref(tall), p[0], p[1], p[2], p[3], need - 1, st) == -6
+    wide = sar.RowsDesc.make(256, 20480, p=0.1)   # every slab sees every row: no scratch
+    assert lib.bias_dropout_add_bwd_workspace(ctypes.byref(wide)) == 0
