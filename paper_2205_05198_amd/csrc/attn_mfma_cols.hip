@@ -212,12 +212,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         dkacc[dt][e] += mg[(32 * dt + e) * 64 + lane];
         dvacc[dt][e] += mg[(32 * dt + 16 + e) * 64 + lane];
       }
-    const int key = jw0 + li;
-    if (key < P.s) {
-      store_acc_row<DT>(dk + base + (int64_t)key * P.stride_s, dkacc, P.scale, hh);
-      store_acc_row<DT>(dv + base + (int64_t)key * P.stride_s, dvacc, 1.0f, hh);
-    }
+    acc_to_lds_rows<DT>(smem + 4 * TILE, KP, 32 * kgp + li, dkacc, P.scale, hh);
+    acc_to_lds_rows<DT>(smem + 5 * TILE, KP, 32 * kgp + li, dvacc, 1.0f, hh);
   }
+  __syncthreads();
+  lds_rows_to_global<D>(smem + 4 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
+  lds_rows_to_global<D>(smem + 5 * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
 }
 
 template <int D>

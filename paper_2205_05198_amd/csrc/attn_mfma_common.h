@@ -189,6 +189,37 @@ __device__ __forceinline__ float dot8(bf16x8_t a, bf16x8_t b) {
   return acc;
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Output through LDS.  An accumulator set keeps one tensor row per lane, so storing it directly writes 8-byte
+// pieces of 32 different rows per instruction.  Instead the waves that hold results put them, as bf16, into a
+// 64-row LDS tile (pitch D + 8), and after a barrier all 256 threads copy the tile out with 16-byte accesses that
+// run along the rows.
+// ---------------------------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ void acc_to_lds_rows(uint16_t* tile, int pitch, int row, const float16_t (&acc)[DT], float mul, int hh) {
+  uint16_t* r = tile + row * pitch + 4 * hh;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 w;
+      w.x = pack_bf16x2(acc[dt][4 * g + 0] * mul, acc[dt][4 * g + 1] * mul);
+      w.y = pack_bf16x2(acc[dt][4 * g + 2] * mul, acc[dt][4 * g + 3] * mul);
+      *reinterpret_cast<uint2*>(r + 32 * dt + 8 * g) = w;
+    }
+}
+// rows 0 .. rows_valid-1 of the LDS tile -> global rows g0, g0 + gstride, ...
+template <int D>
+__device__ __forceinline__ void lds_rows_to_global(const uint16_t* tile, uint16_t* g0, int gstride, int rows_valid, int tid) {
+  constexpr int CPR = D / 8, NCH = 64 * CPR, KP = D + 8;
+#pragma unroll
+  for (int it = 0; it < (NCH + 255) / 256; ++it) {
+    const int c = tid + 256 * it, r = c / CPR, cc = c - r * CPR;
+    if (c < NCH && r < rows_valid)
+      *reinterpret_cast<u32x4_t*>(g0 + (int64_t)r * gstride + 8 * cc) = *reinterpret_cast<const u32x4_t*>(tile + r * KP + 8 * cc);
+  }
+}
+
 // store one accumulator set (rows = head-dim columns 32*dt + 8g + 4hh + r of tensor row `row`) as bf16
 template <int DT>
 __device__ __forceinline__ void store_acc_row(uint16_t* row, const float16_t (&acc)[DT], float mul, int hh) {

@@ -206,11 +206,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) oacc[dt][e] = oacc[dt][e] * w0 + mg[(16 * dt + e) * 64 + lane] * w1;
-    if (i < P.s) {
-      store_acc_row<DT>(o + base + (int64_t)i * P.stride_s, oacc, inv, hh);
-      if (hh == 0) lse[(size_t)bn * P.s + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
-    }
+    acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, oacc, inv, hh);
+    if (i < P.s && hh == 0) lse[(size_t)bn * P.s + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
+  __syncthreads();
+  lds_rows_to_global<D>(smem + 2 * TILE, o + base + (int64_t)(rb * BM) * P.stride_s, gstride, P.s - rb * BM, tid);
 }
 
 // ===================================================================================================
@@ -383,8 +383,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int e = 0; e < 16; ++e) dqacc[dt][e] += mg[(16 * dt + e) * 64 + lane];
-    if (i < P.s) store_acc_row<DT>(dq + base + (int64_t)i * P.stride_s, dqacc, P.scale, hh);
+    acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, dqacc, P.scale, hh);
   }
+  __syncthreads();
+  lds_rows_to_global<D>(smem + 2 * TILE, dq + base + (int64_t)(rb * BM) * P.stride_s, gstride, P.s - rb * BM, tid);
 }
 
 bool attn_mfma_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 160; }
