@@ -195,23 +195,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
   __syncthreads();
   float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
   if (is == 1) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        mg[(32 * dt + e) * 64 + lane] = dkacc[dt][e];
-        mg[(32 * dt + 16 + e) * 64 + lane] = dvacc[dt][e];
-      }
+    acc_put<DT>(mg, dkacc, lane);
+    acc_put<DT>(mg + 16 * DT * 64, dvacc, lane);
   }
   __syncthreads();
   if (is == 0) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        dkacc[dt][e] += mg[(32 * dt + e) * 64 + lane];
-        dvacc[dt][e] += mg[(32 * dt + 16 + e) * 64 + lane];
-      }
+    acc_combine<DT>(mg, dkacc, 1.f, 1.f, lane);
+    acc_combine<DT>(mg + 16 * DT * 64, dvacc, 1.f, 1.f, lane);
     acc_to_lds_rows<DT>(smem + 4 * TILE, KP, 32 * kgp + li, dkacc, P.scale, hh);
     acc_to_lds_rows<DT>(smem + 5 * TILE, KP, 32 * kgp + li, dvacc, 1.0f, hh);
   }

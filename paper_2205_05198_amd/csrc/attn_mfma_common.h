@@ -220,6 +220,34 @@ __device__ __forceinline__ void lds_rows_to_global(const uint16_t* tile, uint16_
   }
 }
 
+// Exchange of accumulator sets between two waves through LDS, 16 bytes per lane and access: slot (4*dt + g) of
+// lane `lane` holds acc[dt][4g .. 4g+3].  buf must hold 16 * DT * 64 floats.
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+template <int DT>
+__device__ __forceinline__ void acc_put(float* buf, const float16_t (&acc)[DT], int lane) {
+  f32x4_t* b = reinterpret_cast<f32x4_t*>(buf) + lane;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      f32x4_t v = {acc[dt][4 * g], acc[dt][4 * g + 1], acc[dt][4 * g + 2], acc[dt][4 * g + 3]};
+      b[(4 * dt + g) * 64] = v;
+    }
+}
+// acc = acc * w0 + other * w1
+template <int DT>
+__device__ __forceinline__ void acc_combine(const float* buf, float16_t (&acc)[DT], float w0, float w1, int lane) {
+  const f32x4_t* b = reinterpret_cast<const f32x4_t*>(buf) + lane;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const f32x4_t v = b[(4 * dt + g) * 64];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[dt][4 * g + r] = acc[dt][4 * g + r] * w0 + v[r] * w1;
+    }
+}
+
 // store one accumulator set (rows = head-dim columns 32*dt + 8g + 4hh + r of tensor row `row`) as bf16
 template <int DT>
 __device__ __forceinline__ void store_acc_row(uint16_t* row, const float16_t (&acc)[DT], float mul, int hh) {

@@ -188,10 +188,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   __syncthreads();
   float* mg = reinterpret_cast<float*>(smem) + rg * (64 * (16 * DT + 2));
   if (ks == 1) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mg[(16 * dt + e) * 64 + lane] = oacc[dt][e];
+    acc_put<DT>(mg, oacc, lane);
     mg[(16 * DT) * 64 + lane] = m_ref;
     mg[(16 * DT + 1) * 64 + lane] = l_tot;
   }
@@ -202,10 +199,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
     const float w0 = __builtin_amdgcn_exp2f(m_ref - m), w1 = __builtin_amdgcn_exp2f(m1 - m);
     const float l = l_tot * w0 + l1 * w1;
     const float inv = P.keep_scale / l;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[dt][e] = oacc[dt][e] * w0 + mg[(16 * dt + e) * 64 + lane] * w1;
+    acc_combine<DT>(mg, oacc, w0, w1, lane);
     acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, oacc, inv, hh);
     if (i < P.s && hh == 0) lse[(size_t)bn * P.s + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
@@ -371,18 +365,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
   // ---- sum the two key halves, scale, store ----
   __syncthreads();
   float* mg = reinterpret_cast<float*>(smem) + rg * (64 * 16 * DT);
-  if (ks == 1) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) mg[(16 * dt + e) * 64 + lane] = dqacc[dt][e];
-  }
+  if (ks == 1) acc_put<DT>(mg, dqacc, lane);
   __syncthreads();
   if (ks == 0) {
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) dqacc[dt][e] += mg[(16 * dt + e) * 64 + lane];
+    acc_combine<DT>(mg, dqacc, 1.f, 1.f, lane);
     acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, dqacc, P.scale, hh);
   }
   __syncthreads();
