@@ -175,8 +175,11 @@ def main():
             e[1].record()
             torch.cuda.synchronize()
             st_ms = e[0].elapsed_time(e[1]) / args.stored_steps
+            extra = 2 * 5 * N * s * s   # P, M, D written by the forward and read by the backward (Section 4.1: 5 a s^2 b / t each way)
             stored = {"fwd_bwd_ms": st_ms, "recompute_over_stored": attn_ms / st_ms,
-                      "kind": "plain fp32-arithmetic kernels that write/read P, M, D (5 a s^2 b / t bytes)"}
+                      "kind": "plain fp32-arithmetic kernels that write/read P, M, D (5 a s^2 b / t bytes); not a tuned path",
+                      "extra_hbm_bytes": extra, "extra_hbm_ms_at_peak": extra / (PEAK_HBM_GBS * 1e9) * 1e3,
+                      "note": "any stored path pays extra_hbm_ms_at_peak on top of 6 of the 7 contractions timed here"}
             del Pst, Dst, Mst
         except Exception as ex:  # noqa: BLE001
             stored = {"error": str(ex)}
