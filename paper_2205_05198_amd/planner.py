@@ -98,3 +98,38 @@ def plan(mod: Model, lay: Layout, activation_budget_bytes: int, sequence_paralle
         if r["bytes"] <= activation_budget_bytes:
             return {**r, "fits": True, "considered": rows}
     return {**rows[-1], "fits": False, "considered": rows}
+
+
+def outstanding_microbatches(lay: Layout, stage: int) -> int:
+    """Appendix C: microbatches whose back-propagation is still outstanding at pipeline stage `stage`
+    (0 = first) in the non-interleaved 1F1B schedule: max(0, p - S)."""
+    if stage < 0:
+        raise ValueError("stage must be >= 0")
+    return max(0, lay.p - stage)
+
+
+def microbatch_level_plan(mod: Model, lay: Layout, stage: int, activation_budget_bytes: int,
+                          checkpointed: str = "tp_sp_selective", stored: str = "tp_sp") -> dict:
+    """Appendix C, microbatch-level recomputation: of the w = max(0, p - S) microbatches in flight at a stage, keep
+    all activations of as many as the budget allows (`stored` strategy) and checkpoint the rest (`checkpointed`
+    strategy); the stored ones form a moving window, so in steady state the same share of all microbatches runs
+    without recomputation.  A stage holds L/p layers per microbatch (embedding and output-layer extras are left to
+    first_stage_activation_bytes).  Returns the window, the number stored in full, the bytes used, the share of
+    microbatches that recompute and the resulting executed-FLOPs overhead; 'fits' is False if even checkpointing
+    every microbatch exceeds the budget."""
+    if lay.m != 1:
+        raise ValueError("Appendix C describes the non-interleaved schedule (m = 1)")
+    w = outstanding_microbatches(lay, stage)
+    layers = Fraction(mod.L, lay.p)
+    full = layer_activation_bytes(mod, lay, stored) * layers
+    ckpt = layer_activation_bytes(mod, lay, checkpointed) * layers
+    if full < ckpt:
+        raise ValueError("the stored strategy must keep at least what the checkpointed one keeps")
+    over = flops_overhead(mod, checkpointed)
+    if w == 0:
+        return {"window": 0, "stored_in_full": 0, "bytes": Fraction(0), "recompute_share": Fraction(0), "flops_overhead": Fraction(0), "fits": True}
+    if w * ckpt > activation_budget_bytes:
+        return {"window": w, "stored_in_full": 0, "bytes": w * ckpt, "recompute_share": Fraction(1), "flops_overhead": over, "fits": False}
+    k = w if full == ckpt else min(w, int((activation_budget_bytes - w * ckpt) // (full - ckpt)))
+    share = Fraction(w - k, w)
+    return {"window": w, "stored_in_full": k, "bytes": k * full + (w - k) * ckpt, "recompute_share": share, "flops_overhead": share * over, "fits": True}

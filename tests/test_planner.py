@@ -79,3 +79,29 @@ def test_interleaving_and_plan():
     assert pl.plan(mod, lay, int(lo) - 1)["strategy"] == "full"
     assert not pl.plan(mod, lay, 1000)["fits"]
     assert pl.plan(mod, lay, int((lo + hi) / 2), sequence_parallel=False)["strategy"] in ("tp_selective", "full")
+
+
+def test_microbatch_level_window_and_share():
+    """Appendix C: max(0, p - S) microbatches are in flight at stage S; the figure's example (p = 4) keeps one of
+    the first stage's four microbatches in full when the memory left over after checkpointing all four holds
+    exactly one more full set; later stages need less and the last ones nothing."""
+    from paper_2205_05198_amd.planner import Layout, Model, layer_activation_bytes, microbatch_level_plan, outstanding_microbatches, flops_overhead
+    mod, lay = Model(h=12288, a=96, L=96), Layout(b=1, t=8, p=4)
+    assert [outstanding_microbatches(lay, S) for S in range(6)] == [4, 3, 2, 1, 0, 0]
+    layers = mod.L // lay.p
+    full = layer_activation_bytes(mod, lay, "tp_sp") * layers
+    ck = layer_activation_bytes(mod, lay, "tp_sp_selective") * layers
+    budget = int(4 * ck + (full - ck))            # all four checkpointed + room to keep one of them in full
+    r = microbatch_level_plan(mod, lay, 0, budget)
+    assert (r["window"], r["stored_in_full"], r["fits"]) == (4, 1, True)
+    assert r["bytes"] == full + 3 * ck and r["bytes"] <= budget
+    assert r["recompute_share"] == Fraction(3, 4) and r["flops_overhead"] == Fraction(3, 4) * flops_overhead(mod, "tp_sp_selective")
+    assert microbatch_level_plan(mod, lay, 0, budget - 1)["stored_in_full"] == 0      # one byte short: none fits in full
+    # the same budget stores more microbatches in full at later stages, and every one from some stage on
+    ks = [microbatch_level_plan(mod, lay, S, budget) for S in range(5)]
+    assert [k["window"] - k["stored_in_full"] for k in ks] == sorted((k["window"] - k["stored_in_full"] for k in ks), reverse=True)
+    assert ks[3]["recompute_share"] == 0 and ks[4] == {"window": 0, "stored_in_full": 0, "bytes": 0, "recompute_share": 0, "flops_overhead": 0, "fits": True}
+    # too small even for checkpointing everything
+    assert microbatch_level_plan(mod, lay, 0, int(4 * ck) - 1)["fits"] is False
+    # first-stage bytes with nothing stored in full are the L-layer figure of Eq. 6 without the embedding terms
+    assert microbatch_level_plan(mod, lay, 0, int(4 * ck))["bytes"] == layer_activation_bytes(mod, lay, "tp_sp_selective") * mod.L
