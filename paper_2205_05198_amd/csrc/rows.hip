@@ -100,90 +100,108 @@ __global__ __launch_bounds__(1024) void ln_fwd_kernel(RowsParams P, const T* __r
 }
 
 // ---------------------------------------------------------------------------------------------------
-// LayerNorm backward, pass 1: per row c1 = mean_c(g), c2 = mean_c(g xhat) with g = dy*gamma.
+// LayerNorm backward, one launch with two kinds of workgroups (dgamma / dbeta do not depend on the row sums, so
+// nothing orders the two kinds):
+//   blockIdx <  rows: one row, kept in registers: c1 = mean_c(g), c2 = mean_c(g xhat) with g = dy*gamma, then
+//                     dx = rstd (g - c1 - xhat c2);
+//   blockIdx >= rows: a slab of kLnSlab columns and a contiguous range of rows (kLnSlab/8 lanes cover one row segment,
+//                     8 blockDim/kLnSlab segments per trip): dgamma = sum_r dy xhat, dbeta = sum_r dy of the slab, summed in
+//                     registers, across the lanes of a wave, then across waves in LDS.  The second read of x and dy
+//                     comes out of the caches: the row workgroups stream the same bytes at the same time.
+// part[split][0][h] = dgamma partial, part[split][1][h] = dbeta partial (or the final arrays if there is 1 split).
 // ---------------------------------------------------------------------------------------------------
+constexpr int kLnSlab = 64;  // columns of a slab workgroup: 8 lanes x 16 bytes (bf16) per row segment; 128 measured slower
+
 template <typename T, int VPT>
-__global__ __launch_bounds__(1024) void ln_bwd_rowstats_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
-                                                              const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                              const T* __restrict__ gamma, float2* __restrict__ rowstat) {
+__global__ __launch_bounds__(1024) void ln_bwd_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     const T* __restrict__ gamma, T* __restrict__ dx, float* __restrict__ dg_out,
+                                                     float* __restrict__ db_out, int nslab, int rows_per_split) {
   __shared__ float red[32];
-  const int64_t r = blockIdx.x;
-  const int nchunk = (int)(P.h >> 3);
-  const float mu = mean[r], rs = rstd[r];
-  float s1 = 0.f, s2 = 0.f;
+  __shared__ float sacc[2][16][kLnSlab];
+  if ((int64_t)blockIdx.x < P.rows) {
+    const int64_t r = blockIdx.x;
+    const int nchunk = (int)(P.h >> 3);
+    const float mu = mean[r], rs = rstd[r];
+    float xh[VPT][8], gg[VPT][8];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-  for (int u = 0; u < VPT; ++u) {
-    const int c = threadIdx.x + u * blockDim.x;
-    if (c < nchunk) {
-      float xv[8], dv[8], g[8];
-      Vec8<T>::load(x + r * P.h + 8 * c, xv);
-      Vec8<T>::load(dy + r * P.h + 8 * c, dv);
-      Vec8<T>::load(gamma + 8 * c, g);
+    for (int u = 0; u < VPT; ++u) {
+      const int c = threadIdx.x + u * blockDim.x;
+      if (c < nchunk) {
+        float xv[8], dv[8], g[8];
+        Vec8<T>::load(x + r * P.h + 8 * c, xv);
+        Vec8<T>::load(dy + r * P.h + 8 * c, dv);
+        Vec8<T>::load(gamma + 8 * c, g);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float gg = dv[e] * g[e];
-        s1 += gg;
-        s2 = fmaf(gg, (xv[e] - mu) * rs, s2);
+        for (int e = 0; e < 8; ++e) {
+          xh[u][e] = (xv[e] - mu) * rs;
+          gg[u][e] = dv[e] * g[e];
+          s1 += gg[u][e];
+          s2 = fmaf(gg[u][e], xh[u][e], s2);
+        }
       }
     }
+    block_sum2(s1, s2, red);
+    const float c1 = s1 / (float)P.h, c2 = s2 / (float)P.h;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+      const int c = threadIdx.x + u * blockDim.x;
+      if (c < nchunk) {
+        float out[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = rs * (gg[u][e] - c1 - xh[u][e] * c2);
+        Vec8<T>::store(dx + r * P.h + 8 * c, out);
+      }
+    }
+    return;
   }
-  block_sum2(s1, s2, red);
-  if (threadIdx.x == 0) rowstat[r] = make_float2(s1 / (float)P.h, s2 / (float)P.h);
-}
-
-// ---------------------------------------------------------------------------------------------------
-// LayerNorm backward, pass 2: a workgroup owns a slab of 64 columns and a contiguous range of rows.
-// 8 lanes cover one row segment (64 columns), 32 row segments per step.  dx is written in place of the
-// row formula; dgamma / dbeta of the slab are summed over the workgroup's rows in registers, then in LDS.
-// part[split][0][h] = dgamma partial, part[split][1][h] = dbeta partial (or the final arrays if 1 split).
-// ---------------------------------------------------------------------------------------------------
-template <typename T>
-__global__ __launch_bounds__(256) void ln_bwd_slab_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
-                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
-                                                         const T* __restrict__ gamma, const float2* __restrict__ rowstat, T* __restrict__ dx,
-                                                         float* __restrict__ dg_out, float* __restrict__ db_out, int rows_per_split) {
-  __shared__ float sg[32][65], sb[32][65];
-  const int slab = blockIdx.x, split = blockIdx.y;
-  const int seg = threadIdx.x >> 3, l8 = threadIdx.x & 7;
-  const int64_t col = (int64_t)slab * 64 + 8 * l8;
+  const int idx = (int)((int64_t)blockIdx.x - P.rows);
+  const int slab = idx % nslab, split = idx / nslab;
+  constexpr int LPS = kLnSlab / 8;  // lanes per row segment
+  const int nseg = (int)(blockDim.x / LPS), seg = threadIdx.x / LPS, ls = threadIdx.x % LPS;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, nw = (int)(blockDim.x >> 6);
+  const int64_t col = (int64_t)slab * kLnSlab + 8 * ls;
   const bool colok = col < P.h;
   const int64_t r_lo = (int64_t)split * rows_per_split;
   const int64_t r_hi = min(P.rows, r_lo + rows_per_split);
-  float g[8], ag[8], ab[8];
+  float ag[8], ab[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { ag[e] = 0.f; ab[e] = 0.f; g[e] = 0.f; }
-  if (colok) Vec8<T>::load(gamma + col, g);
-  for (int64_t r = r_lo + seg; r < r_hi; r += 32) {
-    if (colok) {
-      float xv[8], dv[8], out[8];
+  for (int e = 0; e < 8; ++e) { ag[e] = 0.f; ab[e] = 0.f; }
+  if (colok) {
+    for (int64_t r = r_lo + seg; r < r_hi; r += nseg) {
+      float xv[8], dv[8];
       Vec8<T>::load(x + r * P.h + col, xv);
       Vec8<T>::load(dy + r * P.h + col, dv);
       const float mu = mean[r], rs = rstd[r];
-      const float2 st = rowstat[r];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        float xh = (xv[e] - mu) * rs;
-        float gg = dv[e] * g[e];
-        out[e] = rs * (gg - st.x - xh * st.y);
-        ag[e] = fmaf(dv[e], xh, ag[e]);
+        ag[e] = fmaf(dv[e], (xv[e] - mu) * rs, ag[e]);
         ab[e] += dv[e];
       }
-      Vec8<T>::store(dx + r * P.h + col, out);
     }
   }
+  // lanes ls, ls + LPS, ... of a wave hold the same columns
 #pragma unroll
-  for (int e = 0; e < 8; ++e) { sg[seg][8 * l8 + e] = ag[e]; sb[seg][8 * l8 + e] = ab[e]; }
-  __syncthreads();
-  if (threadIdx.x < 128) {
-    const int c = threadIdx.x & 63;
-    const bool isb = threadIdx.x >= 64;
-    float t = 0.f;
-    for (int q = 0; q < 32; ++q) t += isb ? sb[q][c] : sg[q][c];
-    const int64_t cc = (int64_t)slab * 64 + c;
-    if (cc < P.h) {
-      float* dst = isb ? db_out : dg_out;
-      dst[(size_t)split * 2 * P.h + cc] = t;
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int m = LPS; m < 64; m <<= 1) {
+      ag[e] += __shfl_xor(ag[e], m);
+      ab[e] += __shfl_xor(ab[e], m);
     }
+  }
+  if (lane < LPS) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { sacc[0][wave][8 * ls + e] = ag[e]; sacc[1][wave][8 * ls + e] = ab[e]; }
+  }
+  __syncthreads();
+  // thread t sums array t / kLnSlab, column t % kLnSlab over the waves
+  for (int t = threadIdx.x; t < 2 * kLnSlab; t += blockDim.x) {
+    const int c = t % kLnSlab, which = t / kLnSlab;
+    float tot = 0.f;
+    for (int q = 0; q < nw; ++q) tot += sacc[which][q][c];
+    const int64_t cc = (int64_t)slab * kLnSlab + c;
+    if (cc < P.h) (which ? db_out : dg_out)[(size_t)split * 2 * P.h + cc] = tot;
   }
 }
 
@@ -404,10 +422,11 @@ hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const vo
   return bf16 ? ln_fwd_t<uint16_t>(P, x, gamma, beta, y, mean, rstd, st) : ln_fwd_t<float>(P, x, gamma, beta, y, mean, rstd, st);
 }
 
-static inline void ln_bwd_plan(int64_t rows, int64_t h, int& nslab, int& nsplit, int& rows_per_split) {
-  nslab = (int)((h + 63) / 64);
-  int want = (256 + nslab - 1) / nslab;                  // aim at >= 256 workgroups (one per CU)
-  int maxsplit = (int)((rows + 31) / 32);                 // at least one 32-row step per split
+static inline void ln_bwd_plan(int64_t rows, int64_t h, int threads, int slabw, int& nslab, int& nsplit, int& rows_per_split) {
+  nslab = (int)((h + slabw - 1) / slabw);
+  const int nseg = threads / (slabw / 8);                // row segments per trip of a slab workgroup
+  int want = (256 + nslab - 1) / nslab;                  // aim at >= 256 slab workgroups (one per CU)
+  int maxsplit = (int)((rows + nseg - 1) / nseg);         // at least one full trip per split
   nsplit = want < 1 ? 1 : (want > maxsplit ? maxsplit : want);
   if (nsplit < 1) nsplit = 1;
   rows_per_split = (int)((rows + nsplit - 1) / nsplit);
@@ -415,42 +434,33 @@ static inline void ln_bwd_plan(int64_t rows, int64_t h, int& nslab, int& nsplit,
 }
 
 size_t ln_bwd_workspace_bytes(int64_t rows, int64_t h) {
-  int nslab, nsplit, rps;
-  ln_bwd_plan(rows, h, nslab, nsplit, rps);
-  size_t rowstat = ((size_t)rows * sizeof(float2) + 255) / 256 * 256;
-  return rowstat + (size_t)nsplit * 2 * (size_t)h * sizeof(float);
+  int nslab, nsplit, rps, threads;
+  pick_vpt(h, threads);
+  ln_bwd_plan(rows, h, threads, kLnSlab, nslab, nsplit, rps);
+  return nsplit > 1 ? (size_t)nsplit * 2 * (size_t)h * sizeof(float) : 256;
 }
 
 template <typename T>
 static hipError_t ln_bwd_t(const RowsParams& P, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma, void* dx,
                            float* dgamma, float* dbeta, void* ws, hipStream_t st) {
-  int nslab, nsplit, rps;
-  ln_bwd_plan(P.rows, P.h, nslab, nsplit, rps);
-  float2* rowstat = (float2*)ws;
-  float* part = (float*)((char*)ws + ((size_t)P.rows * sizeof(float2) + 255) / 256 * 256);
-  int threads;
+  int nslab, nsplit, rps, threads;
   const int vpt = pick_vpt(P.h, threads);
-  dim3 grid((unsigned)P.rows), block(threads);
-#define SAR_LN_RS(V) hipLaunchKernelGGL((ln_bwd_rowstats_kernel<T, V>), grid, block, 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, rowstat)
+  ln_bwd_plan(P.rows, P.h, threads, kLnSlab, nslab, nsplit, rps);
+  float* part = (float*)ws;
+  // one split: the slab workgroups see every row and write dgamma / dbeta themselves; else partials [split][2][h]
+  float* dg_out = nsplit == 1 ? dgamma : part;
+  float* db_out = nsplit == 1 ? dbeta : part + P.h;
+  dim3 grid((unsigned)(P.rows + (int64_t)nslab * nsplit)), block(threads);
+#define SAR_LN_BWD(V) hipLaunchKernelGGL((ln_bwd_kernel<T, V>), grid, block, 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma, (T*)dx, dg_out, db_out, nslab, rps)
   switch (vpt) {
-    case 1: SAR_LN_RS(1); break;
-    case 2: SAR_LN_RS(2); break;
-    case 3: SAR_LN_RS(3); break;
-    default: SAR_LN_RS(4); break;
+    case 1: SAR_LN_BWD(1); break;
+    case 2: SAR_LN_BWD(2); break;
+    case 3: SAR_LN_BWD(3); break;
+    default: SAR_LN_BWD(4); break;
   }
-#undef SAR_LN_RS
+#undef SAR_LN_BWD
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  if (nsplit == 1) {  // one workgroup per column slab sees every row: it writes dgamma / dbeta itself
-    hipLaunchKernelGGL((ln_bwd_slab_kernel<T>), dim3(nslab, 1), dim3(256), 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma,
-                       (const float2*)rowstat, (T*)dx, dgamma, dbeta, rps);
-    return hipGetLastError();
-  }
-  // partial layout [split][2][h]: dgamma part at +0, dbeta part at +h
-  hipLaunchKernelGGL((ln_bwd_slab_kernel<T>), dim3(nslab, nsplit), dim3(256), 0, st, P, (const T*)dy, (const T*)x, mean, rstd, (const T*)gamma,
-                     (const float2*)rowstat, (T*)dx, part, part + P.h, rps);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || nsplit == 1) return e;
   hipLaunchKernelGGL(ln_bwd_finish_kernel, dim3((unsigned)((P.h + 255) / 256)), dim3(256), 0, st, (const float*)part, nsplit, P.h, dgamma, dbeta);
   return hipGetLastError();
 }
@@ -507,7 +517,7 @@ hipError_t launch_bias_dropout_add_ln_fwd(const RowsParams& P, bool bf16, const 
 
 size_t bda_bwd_workspace_bytes(int64_t rows, int64_t h) {
   int nslab, nsplit, rps;
-  ln_bwd_plan(rows, h, nslab, nsplit, rps);
+  ln_bwd_plan(rows, h, 256, 64, nslab, nsplit, rps);
   return nsplit > 1 ? (size_t)nsplit * (size_t)h * sizeof(float) : 0;
 }
 
@@ -519,7 +529,7 @@ static hipError_t bda_bwd_t(const RowsParams& P, const void* dout, void* dx, flo
     return hipGetLastError();
   }
   int nslab, nsplit, rps;
-  ln_bwd_plan(P.rows, P.h, nslab, nsplit, rps);
+  ln_bwd_plan(P.rows, P.h, 256, 64, nslab, nsplit, rps);
   if (nsplit == 1) {
     hipLaunchKernelGGL((bda_bwd_slab_kernel<T>), dim3(nslab, 1), dim3(256), 0, st, P, (const T*)dout, (T*)dx, dbias, rps);
     return hipGetLastError();
