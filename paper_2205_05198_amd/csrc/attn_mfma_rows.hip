@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
   // These must have arrived before the tile loop: a wait left inside the loop would also wait for the direct
   // loads in flight there, which the compiler does not know about.
 #pragma unroll
-  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[kc]), "+v"(dof[kc]));
+  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+a"(qf[kc]), "+a"(dof[kc]));
   const float dl = dpart + __shfl_xor(dpart, 32, 64);
   if (ks == 0 && hh == 0 && i < P.s) delta[(size_t)bn * P.s + i] = dl;
   const float lse2 = lse[(size_t)bn * P.s + i_ld] * kLog2e;
@@ -296,7 +296,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
       dma_tile<D>(map, vn, nxt + TILE, wave);
     }
     const int j0w = j0 + 32 * ks;
-    if (j0w <= lim_hi) {
+    {
+      // a wave whose keys all lie past its rows (upper half of the diagonal tile) runs the step fully masked: the
+      // other waves of the tile work meanwhile, so skipping would gain nothing, and one path through the step
+      // keeps the accumulators in place
       const bool diag = (j0w + 31 > lim_lo);  // some of the wave's keys are masked for some of its rows
       float16_t st, dd;
 #pragma unroll
@@ -349,9 +352,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
       for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) dqacc[dt] = mfma32(ld_frag_tr_perm(Ks, KP, 32 * ks + 16 * c, 32 * dt, lane), dsf[c], dqacc[dt]);
-    } else if (MODE == 1 && wave != 0) {
-      dma_tile<D>(map, kn, nxt, wave);
-      dma_tile<D>(map, vn, nxt + TILE, wave);
     }
   };
   {
