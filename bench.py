@@ -5,8 +5,9 @@ A step = one pass of the whole hot path over one synthetic batch of the 530B-cla
 (h=20480, a=128, t=8, s=2048, b=1: 16 heads x head_dim 160; sequence-parallel rows 256 x 20480):
 attn_core_fwd, attn_core_bwd_recompute (row pass + column pass), ln_fwd, ln_bwd, bias_dropout_add.
 `value` is the attention core's algorithmic fwd+bwd FLOPs (14 d T N, causal: T = s(s+1)/2) per second of
-whole-step time.  Per-kernel durations come from HIP events recorded between the launches of the timed
-steps, on the stream the kernels run on.
+whole-step time.  The dominant kernel (dK/dV pass) is bracketed by HIP events inside the timed steps (every 4th
+step: an event record costs stream time), on the stream the kernels run on; the other kernels' durations come
+from a second, untimed pass with events between all launches.
 """
 import argparse
 import json
@@ -73,23 +74,21 @@ def main():
 
     names = ["attn_core_fwd", "attn_bwd_dq", "attn_bwd_dkdv", "ln_fwd", "ln_bwd", "bias_dropout_add"]
 
-    def step(events=None):
-        def mark(i):
-            if events is not None:
+    DOM = 2   # the dK/dV pass executes 4 of the 7 contractions: the dominant kernel, timed inside the timed region
+
+    def step(events=None, marks=range(7)):
+        calls = (lambda: sar.attn_core_fwd(desc, tq, tk, tv, o, lse),
+                 lambda: sar.attn_core_bwd_recompute_dq(desc, tq, tk, tv, o, lse, tdo, dq, ws),
+                 lambda: sar.attn_core_bwd_recompute_dkdv(desc, tq, tk, tv, lse, tdo, dk, dv, ws),
+                 lambda: sar.ln_fwd(rdesc, x, gamma, beta, y, mean, rstd),
+                 lambda: sar.ln_bwd(rdesc, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws2),
+                 lambda: sar.bias_dropout_add(rdesc, x, bias, resid, out, None))
+        for i, call in enumerate(calls):
+            if events is not None and i in marks:
                 events[i].record()
-        mark(0)
-        sar.attn_core_fwd(desc, tq, tk, tv, o, lse)
-        mark(1)
-        sar.attn_core_bwd_recompute_dq(desc, tq, tk, tv, o, lse, tdo, dq, ws)
-        mark(2)
-        sar.attn_core_bwd_recompute_dkdv(desc, tq, tk, tv, lse, tdo, dk, dv, ws)
-        mark(3)
-        sar.ln_fwd(rdesc, x, gamma, beta, y, mean, rstd)
-        mark(4)
-        sar.ln_bwd(rdesc, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws2)
-        mark(5)
-        sar.bias_dropout_add(rdesc, x, bias, resid, out, None)
-        mark(6)
+            call()
+        if events is not None and 6 in marks:
+            events[6].record()
 
     if args.calibrate_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -101,15 +100,25 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # Timed region: exactly `steps` steps.  An event record costs about 4 us of stream time here, so inside the timed
+    # region only the dominant kernel is bracketed, on every 4th step; the other kernels are timed in a second pass
+    # that does not count towards `value`.
+    SAMPLE = 4
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(evs[i])
+        step(evs[i] if i % SAMPLE == 0 else None, marks=(DOM, DOM + 1))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = {n: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(args.steps)])) for j, n in enumerate(names)}
+    dom_ms = float(np.mean([evs[i][DOM].elapsed_time(evs[i][DOM + 1]) for i in range(0, args.steps, SAMPLE)]))
+    nb = min(args.steps, 50)
+    for i in range(nb):
+        step(evs[i])
+    torch.cuda.synchronize()
+    kern_ms = {n: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(nb)])) for j, n in enumerate(names)}
+    kern_ms[names[DOM]] = dom_ms
 
     # algorithmic work (causal: T = s(s+1)/2 score pairs per head; every key: s^2)
     T = s * (s + 1) // 2 if w.causal else s * s
@@ -124,8 +133,8 @@ def main():
     }
     value = flops_alg_fwd_bwd / (ms_per_step * 1e-3) / 1e12
     attn_ms = kern_ms["attn_core_fwd"] + kern_ms["attn_bwd_dq"] + kern_ms["attn_bwd_dkdv"]
-    dom = max(("attn_core_fwd", "attn_bwd_dq", "attn_bwd_dkdv"), key=lambda n: kern_ms[n])
-    achieved = flops[dom] / (kern_ms[dom] * 1e-3) / 1e12
+    dom = names[DOM]
+    achieved = flops[dom] / (dom_ms * 1e-3) / 1e12
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
