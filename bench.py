@@ -29,7 +29,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="530B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stored-steps", type=int, default=2, help="steps of the stored-activation baseline (0 = skip)")
+    ap.add_argument("--stored-steps", type=int, default=20, help="steps of the stored-activation baseline (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known traffic) so that FETCH_SIZE / WRITE_SIZE of a rocprofv3 --pmc run can be scaled")
     args = ap.parse_args()
@@ -173,22 +173,30 @@ def main():
             Pst = torch.empty((b, A, s, s), dtype=torch.bfloat16, device="cuda")
             Dst = torch.empty_like(Pst)
             Mst = torch.empty((b, A, s, s), dtype=torch.uint8, device="cuda")
-            e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            sar.attn_core_fwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst)
-            sar.attn_core_bwd_stored(desc, tq, tk, tv, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            for _ in range(2):
+                sar.attn_core_fwd_stored(desc, tq, tk, tv, o, lse, Pst, Mst, Dst)
+                sar.attn_core_bwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
             torch.cuda.synchronize()
             e[0].record()
             for _ in range(args.stored_steps):
-                sar.attn_core_fwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst)
-                sar.attn_core_bwd_stored(desc, tq, tk, tv, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
+                sar.attn_core_fwd_stored(desc, tq, tk, tv, o, lse, Pst, Mst, Dst)
             e[1].record()
+            for _ in range(args.stored_steps):
+                sar.attn_core_bwd_stored(desc, tq, tk, tv, o, Pst, Mst, Dst, tdo, dq, dk, dv, ws)
+            e[2].record()
             torch.cuda.synchronize()
-            st_ms = e[0].elapsed_time(e[1]) / args.stored_steps
+            st_fwd = e[0].elapsed_time(e[1]) / args.stored_steps
+            st_bwd = e[1].elapsed_time(e[2]) / args.stored_steps
+            st_ms = st_fwd + st_bwd
             extra = 2 * 5 * N * s * s   # P, M, D written by the forward and read by the backward (Section 4.1: 5 a s^2 b / t each way)
-            stored = {"fwd_bwd_ms": st_ms, "recompute_over_stored": attn_ms / st_ms,
-                      "kind": "plain fp32-arithmetic kernels that write/read P, M, D (5 a s^2 b / t bytes); not a tuned path",
+            mfma_stored = w.d in (64, 96, 128, 160) and s % 64 == 0
+            stored = {"fwd_bwd_ms": st_ms, "fwd_ms": st_fwd, "bwd_ms": st_bwd, "recompute_over_stored": attn_ms / st_ms,
+                      "kind": ("matrix-core kernels on the tiles of the recompute path: forward = recompute forward + a pass that writes P, M, D "
+                               "(scores computed twice), backward reads P, M (row pass) and P, M, D (column pass)") if mfma_stored else
+                              "plain fp32-arithmetic kernels that write/read P, M, D; not a tuned path",
                       "extra_hbm_bytes": extra, "extra_hbm_ms_at_peak": extra / (PEAK_HBM_GBS * 1e9) * 1e3,
-                      "note": "any stored path pays extra_hbm_ms_at_peak on top of 6 of the 7 contractions timed here"}
+                      "note": "P, M, D: 5 bytes per score element written once and read by both backward passes (M and P twice)"}
             del Pst, Dst, Mst
         except Exception as ex:  # noqa: BLE001
             stored = {"error": str(ex)}

@@ -117,12 +117,17 @@ sar_status attn_core_bwd_recompute_dkdv(const sar_attn_desc* desc, const void* q
  * them back instead of recomputing.  Used for the recompute-vs-stored timing ratio and to expose the
  * mask bit for bit.
  *   P, D : desc->dtype [b, A, s, s];  M : uint8 [b, A, s, s]; entries with j > i are written as 0.
+ *   lse  : out, float [b, A, s], as attn_core_fwd;  o : the forward's output (in, for the backward's
+ *          per-row term delta_i = dO_i . O_i; the plain-kernel path rebuilds that term from P and ignores o).
  * Exactly (2*elem + 1) * A * s^2 * b extra bytes = the paper's 5 a s^2 b / t for 16-bit elements.
+ * bf16 with head dimension 64 / 96 / 128 / 160 and s % 64 == 0 runs on the matrix cores with the tiles of
+ * the recompute kernels (the forward computes the scores twice: once for O and the row statistics, once
+ * to write the normalised P); everything else on the plain kernels.
  * attn_core_bwd_stored takes the same workspace as attn_core_bwd_recompute (per-row softmax term).
  */
 sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
-                                void* o, void* P, uint8_t* M, void* D, void* stream);
-sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                void* o, float* lse, void* P, uint8_t* M, void* D, void* stream);
+sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
                                 const void* P, const uint8_t* M, const void* D, const void* d_o,
                                 void* dq, void* dk, void* dv,
                                 void* workspace, size_t workspace_bytes, void* stream);

@@ -22,6 +22,7 @@ _SOURCES = {
     "attn_simple.hip": [],
     "attn_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
     "attn_mfma_cols.hip": [],
+    "attn_mfma_stored.hip": [],
     "rows.hip": [],
 }
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -115,8 +116,8 @@ def load_library():
         "attn_core_bwd_recompute": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dq": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dkdv": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
-        "attn_core_fwd_stored": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp]),
-        "attn_core_bwd_stored": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "attn_core_fwd_stored": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "attn_core_bwd_stored": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_saved_bytes": (u64, [ad, ctypes.c_int]),
         "attn_core_small_buffer_bytes": (u64, [ad]),
         "attn_core_philox_count": (u64, [ad]),
@@ -187,13 +188,13 @@ def attn_core_bwd_recompute_dkdv(desc: AttnDesc, q, k, v, lse, d_o, dk, dv, work
                                                         _ptr(workspace), nbytes, _stream()))
 
 
-def attn_core_fwd_stored(desc: AttnDesc, q, k, v, o, P, M, D):
-    _check(load_library().attn_core_fwd_stored(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(P), _ptr(M), _ptr(D), _stream()))
+def attn_core_fwd_stored(desc: AttnDesc, q, k, v, o, lse, P, M, D):
+    _check(load_library().attn_core_fwd_stored(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(P), _ptr(M), _ptr(D), _stream()))
 
 
-def attn_core_bwd_stored(desc: AttnDesc, q, k, v, P, M, D, d_o, dq, dk, dv, workspace):
+def attn_core_bwd_stored(desc: AttnDesc, q, k, v, o, P, M, D, d_o, dq, dk, dv, workspace):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(load_library().attn_core_bwd_stored(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(P), _ptr(M), _ptr(D), _ptr(d_o),
+    _check(load_library().attn_core_bwd_stored(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(P), _ptr(M), _ptr(D), _ptr(d_o),
                                                 _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), nbytes, _stream()))
 
 

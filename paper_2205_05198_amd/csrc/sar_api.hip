@@ -162,34 +162,46 @@ sar_status attn_core_bwd_recompute_dkdv(const sar_attn_desc* desc, const void* q
   return bwd_recompute_impl("attn_core_bwd_recompute_dkdv", desc, q, k, v, nullptr, lse, d_o, nullptr, dk, dv, workspace, workspace_bytes, 2, stream);
 }
 
-sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, void* o, void* Pst, uint8_t* Mst, void* Dst,
-                                void* stream) {
+sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse, void* Pst, uint8_t* Mst,
+                                void* Dst, void* stream) {
   sar::AttnParams P;
   sar_status st = check_attn_desc(desc, &P);
   if (st != SAR_OK) return st;
-  if (!q || !k || !v || !o || !Pst || !Mst || !Dst) return fail(SAR_ERR_NULL, "attn_core_fwd_stored: NULL tensor pointer");
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst))
+  if (!q || !k || !v || !o || !lse || !Pst || !Mst || !Dst) return fail(SAR_ERR_NULL, "attn_core_fwd_stored: NULL tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst))
     return fail(SAR_ERR_ALIGN, "attn_core_fwd_stored: pointer not 16-byte aligned");
-  if ((st = check_simple_limits(P)) != SAR_OK) return st;
-  hipError_t e = sar::launch_attn_fwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, nullptr, Pst, Mst, Dst, (hipStream_t)stream);
+  hipError_t e;
+  if (use_mfma(desc, P) && sar::attn_mfma_stored_supported(P)) {
+    e = sar::launch_attn_fwd_mfma(P, q, k, v, o, lse, (hipStream_t)stream);
+    if (e == hipSuccess) e = sar::launch_attn_store_pmd_mfma(P, q, k, lse, Pst, Mst, Dst, (hipStream_t)stream);
+  } else {
+    if ((st = check_simple_limits(P)) != SAR_OK) return st;
+    e = sar::launch_attn_fwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, lse, Pst, Mst, Dst, (hipStream_t)stream);
+  }
   return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_fwd_stored launch");
 }
 
-sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* Pst, const uint8_t* Mst,
-                                const void* Dst, const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
-                                void* stream) {
+sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const void* Pst,
+                                const uint8_t* Mst, const void* Dst, const void* d_o, void* dq, void* dk, void* dv, void* workspace,
+                                size_t workspace_bytes, void* stream) {
   sar::AttnParams P;
   sar_status st = check_attn_desc(desc, &P);
   if (st != SAR_OK) return st;
-  if (!q || !k || !v || !Pst || !Mst || !Dst || !d_o || !dq || !dk || !dv) return fail(SAR_ERR_NULL, "attn_core_bwd_stored: NULL tensor pointer");
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst) || !aligned16(d_o) || !aligned16(dq) ||
-      !aligned16(dk) || !aligned16(dv))
+  if (!q || !k || !v || !o || !Pst || !Mst || !Dst || !d_o || !dq || !dk || !dv) return fail(SAR_ERR_NULL, "attn_core_bwd_stored: NULL tensor pointer");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst) || !aligned16(d_o) ||
+      !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return fail(SAR_ERR_ALIGN, "attn_core_bwd_stored: pointer not 16-byte aligned");
   const size_t need = attn_core_bwd_workspace(desc);
   if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
-  if ((st = check_simple_limits(P)) != SAR_OK) return st;
-  hipError_t e = sar::launch_attn_bwd_simple(P, desc->dtype == SAR_BF16, q, k, v, nullptr, nullptr, d_o, dq, dk, dv, (float*)workspace, Pst, Mst, Dst, 3,
-                                             (hipStream_t)stream);
+  if (!aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
+  hipError_t e;
+  if (use_mfma(desc, P) && sar::attn_mfma_stored_supported(P)) {
+    e = sar::launch_attn_bwd_stored_mfma(P, q, k, v, o, d_o, Pst, Mst, Dst, dq, dk, dv, (float*)workspace, (hipStream_t)stream);
+  } else {
+    if ((st = check_simple_limits(P)) != SAR_OK) return st;
+    e = sar::launch_attn_bwd_simple(P, desc->dtype == SAR_BF16, q, k, v, nullptr, nullptr, d_o, dq, dk, dv, (float*)workspace, Pst, Mst, Dst, 3,
+                                    (hipStream_t)stream);
+  }
   return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_bwd_stored launch");
 }
 

@@ -38,6 +38,13 @@ size_t attn_simple_lds_bytes(int s);
 
 // attn_mfma_rows.hip (forward, dQ pass) and attn_mfma_cols.hip (dK/dV pass): bf16 MFMA kernels, d in {64, 96, 128, 160}
 bool attn_mfma_supported(int d);
+// attn_mfma_stored.hip: the stored-activation baseline on the same tiles (needs s % 64 == 0): P, M, D from Q, K, LSE after
+// the forward; backward passes that read them back
+bool attn_mfma_stored_supported(const AttnParams& P);
+hipError_t launch_attn_store_pmd_mfma(const AttnParams& P, const void* q, const void* k, const float* lse, void* Pst, uint8_t* Mst, void* Dst,
+                                      hipStream_t st);
+hipError_t launch_attn_bwd_stored_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const void* dO, const void* Pst,
+                                       const uint8_t* Mst, const void* Dst, void* dq, void* dk, void* dv, float* delta, hipStream_t st);
 hipError_t launch_attn_fwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, void* o, float* lse, hipStream_t st);
 hipError_t launch_attn_bwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                 const void* dO, void* dq, void* dk, void* dv, float* delta, int passes, hipStream_t st);

@@ -83,10 +83,11 @@ def run_attn(sh, dtype, q, k, v, do, stored=False):
         P = torch.empty((sh.b, sh.A, sh.s, sh.s), dtype=tdt, device="cuda")
         D = torch.empty_like(P)
         M = torch.empty((sh.b, sh.A, sh.s, sh.s), dtype=torch.uint8, device="cuda")
-        sar.attn_core_fwd_stored(desc, dq_, dk_, dv_, o, P, M, D)
-        sar.attn_core_bwd_stored(desc, dq_, dk_, dv_, P, M, D, dd, gq, gk, gv, ws)
+        lse = torch.empty((sh.b, sh.A, sh.s), dtype=torch.float32, device="cuda")
+        sar.attn_core_fwd_stored(desc, dq_, dk_, dv_, o, lse, P, M, D)
+        sar.attn_core_bwd_stored(desc, dq_, dk_, dv_, o, P, M, D, dd, gq, gk, gv, ws)
         torch.cuda.synchronize()
-        out.update(P=host(P), D=host(D), M=M.cpu().numpy())
+        out.update(P=host(P), D=host(D), M=M.cpu().numpy(), lse=host(lse))
     else:
         lse = torch.empty((sh.b, sh.A, sh.s), dtype=torch.float32, device="cuda")
         sar.attn_core_fwd(desc, dq_, dk_, dv_, o, lse)

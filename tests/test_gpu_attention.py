@@ -41,8 +41,6 @@ def _check_bf16_heads(tag, sh, q, k, v, do, got, heads):
             e = err_attn_bf16(got[nm][:, be, n], ref[nm][:, be, n], sc[nm])
             print(f"  {tag}[{bn}] {nm}: {e:.3f} of the bound", flush=True)
             assert e <= 1.0, (tag, bn, nm, e)
-        if "lse" not in got:
-            continue   # the stored path keeps P itself, no log-sum-exp
         lref = ref["lse"][be, n]
         assert np.max(np.abs(got["lse"][be, n] - lref)) < 2e-3 * (1.0 + np.max(np.abs(lref)))
 
@@ -119,6 +117,23 @@ def test_stored_baseline_mask_bit_exact(dtype, d, causal):
         _check("stored", got, {**f, **g}, dtype, ["o", "dq", "dk", "dv"])
     else:
         _check_bf16_heads("stored", sh, q, k, v, do, got, range(4))
+
+
+@pytest.mark.parametrize("d,causal", [(64, 1), (160, 1), (160, 0)])
+def test_stored_baseline_matrix_core_shapes(d, causal):
+    """The stored baseline on the matrix cores (bf16, s a multiple of 64) over several 64-row blocks: M bit-exact, P and D
+    within one bf16 rounding, O, LSE and the gradients to the bf16 bar."""
+    from gpu_util import run_attn
+    s = 320
+    sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=99, offset=8, causal=causal)
+    q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=33)
+    print(f"stored mfma d={d} causal={causal}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, stored=True)
+    f = oracle.attn_fwd(sh, q, k, v, materialise=True)
+    assert np.array_equal(got["M"], f["M"])
+    for nm in ("P", "D"):
+        assert np.max(np.abs(got[nm] - f[nm])) <= 2.0 ** -8, nm
+    _check_bf16_heads("stored-mfma", sh, q, k, v, do, got, range(2))
 
 
 def test_recompute_equals_stored_and_is_deterministic():
