@@ -92,6 +92,29 @@ def test_attention_argument_errors(lib):
     assert lib.attn_core_saved_bytes(None, 1) == 0
 
 
+def test_stored_baseline_argument_errors(lib):
+    """attn_core_fwd_stored / attn_core_bwd_stored reject bad arguments before any launch."""
+    p = _fake(14)
+    st = ctypes.c_void_p(0)
+    d = sar.AttnDesc.packed(s=128, b=1, a=2, h=128)
+    # forward: desc, q, k, v, o, lse, P, M, D
+    assert lib.attn_core_fwd_stored(None, *p[:8], st) == -1
+    for missing in range(8):
+        args = list(p[:8]); args[missing] = None
+        assert lib.attn_core_fwd_stored(ctypes.byref(d), *args, st) == -1, missing
+    args = list(p[:8]); args[5] = ctypes.c_void_p(0x1004)
+    assert lib.attn_core_fwd_stored(ctypes.byref(d), *args, st) == -4
+    assert lib.attn_core_fwd_stored(ctypes.byref(sar.AttnDesc.packed(s=100, b=1, a=2, h=128)), *p[:8], st) == -3
+    # backward: desc, q, k, v, o, P, M, D, dO, dq, dk, dv, workspace, bytes
+    need = lib.attn_core_bwd_workspace(ctypes.byref(d))
+    for missing in range(11):
+        args = list(p[:11]); args[missing] = None
+        assert lib.attn_core_bwd_stored(ctypes.byref(d), *args, p[11], need, st) == -1, missing
+    assert lib.attn_core_bwd_stored(ctypes.byref(d), *p[:11], p[11], need - 1, st) == -6
+    assert lib.attn_core_bwd_stored(ctypes.byref(d), *p[:11], None, need, st) == -6
+    assert lib.attn_core_bwd_stored(ctypes.byref(d), *p[:11], ctypes.c_void_p(0x20008), need, st) == -4
+
+
 def test_rows_argument_errors(lib):
     p = _fake(10)
     st = ctypes.c_void_p(0)
