@@ -63,17 +63,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
   // A operands of S^T and dD^T: LDS row 32*kgp + li holds key jw0 + perm_row(li)
   const uint16_t* kw = Ksm + (32 * kgp + li) * KP + 8 * hh;
   const uint16_t* vw = Vsm + (32 * kgp + li) * KP + 8 * hh;
-#ifdef SAR_KV_REGS
-  bf16x8_t kf[KC], vf[KC];
-  {
-    const int64_t off = base + (int64_t)min(jw0 + perm_row(li), P.s - 1) * P.stride_s + 8 * hh;
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) {
-      kf[kc] = ld_frag(k + off + 16 * kc);
-      vf[kc] = ld_frag(v + off + 16 * kc);
-    }
-  }
-#endif
   // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
   bf16x8_t ident[2];
 #pragma unroll
@@ -124,13 +113,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
-#ifdef SAR_KV_REGS
-        st = mfma32(kf[kc], ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
-        dd = mfma32(vf[kc], ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
-#else
         st = mfma32(ld_frag(kw + 16 * kc), ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
         dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
-#endif
       }
       const int i = i0w + li;
       const float lse2 = lse_c[32 * is + li], dl = delta_c[32 * is + li];

@@ -1,5 +1,5 @@
-// Shared pieces of the bf16 matrix-core attention kernels (attn_mfma_rows.hip, attn_mfma_cols.hip): MFMA wrapper,
-// LDS operand loads, tile staging.
+// Shared pieces of the bf16 matrix-core attention kernels (attn_mfma_rows.hip, attn_mfma_cols.hip, attn_mfma_stored.hip): MFMA wrapper,
+// LDS operand loads, direct global -> LDS tile loads, output staging.
 #pragma once
 #include "sar_device.h"
 #include "sar_internal.h"
@@ -18,17 +18,6 @@ __device__ __forceinline__ float16_t mfma32(bf16x8_t a, bf16x8_t b, float16_t c)
 // 16-byte operand from LDS / global (8 consecutive bf16)
 __device__ __forceinline__ bf16x8_t ld_frag(const uint16_t* p) { return *reinterpret_cast<const bf16x8_t*>(p); }
 
-// Transposed operand: from a row-major tile T[k][c] (pitch in elements) return, for this lane,
-// T[k0 + 8*hh + e][c0 + li], e = 0..7, as one MFMA operand.
-__device__ __forceinline__ bf16x8_t ld_frag_tr(const uint16_t* tile, int pitch, int k0, int c0, int lane) {
-  const int lam = lane & 15, blk = lane >> 4;  // 16-lane block: li = 16*(blk&1) + lam, hh = blk >> 1
-  const uint16_t* p = tile + (k0 + 8 * (blk >> 1) + (lam >> 2)) * pitch + c0 + 16 * (blk & 1) + 4 * (lam & 3);
-  union { short4_t h[2]; bf16x8_t v; } u;
-  u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p));
-  u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(p + 4 * pitch));
-  return u.v;
-}
-
 __device__ __forceinline__ bf16x8_t pack8(const float* f) {
   union { uint32_t w[4]; bf16x8_t v; } u;
   u.w[0] = pack_bf16x2(f[0], f[1]);
@@ -40,50 +29,6 @@ __device__ __forceinline__ bf16x8_t pack8(const float* f) {
 
 // LDS row that holds row r (0..63) of a K tile: bits 2 and 3 swapped inside each group of 32 rows
 __device__ __forceinline__ int perm_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
-
-// ---------------------------------------------------------------------------------------------------
-// Tile staging: a tile is 64 rows x D bf16.  Each of the 256 threads moves ITER 16-byte chunks; the global
-// loads land in registers (tile_fetch) long before they are written to LDS (tile_commit), so that they fly
-// during the previous tile's math.
-// ---------------------------------------------------------------------------------------------------
-template <int D>
-struct TileMap {
-  static constexpr int ROWS = 64, NT = 256, CPR = D / 8, NCH = ROWS * CPR, ITER = NCH / NT;
-  static_assert(NCH % NT == 0, "tile must split evenly over 256 threads");
-  uint32_t goff[ITER];  // BYTE offset of the chunk from the tile's first row in global memory (uniform base + 32-bit lane offset addressing)
-  int loff[ITER];  // element offset of the chunk inside the LDS tile
-  __device__ __forceinline__ void init(int tid, int gstride, int pitch, bool perm) {
-#pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-      const int c = tid + it * NT, r = c / CPR, cc = c - r * CPR;
-      goff[it] = 2u * (uint32_t)(r * gstride + 8 * cc);
-      loff[it] = (perm ? perm_row(r) : r) * pitch + 8 * cc;
-    }
-  }
-};
-template <int D>
-struct TileBuf { u32x4_t r[TileMap<D>::ITER]; };
-
-// gtile points at the tile's first row (uniform); rows_valid = rows of the tensor left from there (clamped reads)
-template <int D>
-__device__ __forceinline__ void tile_fetch(TileBuf<D>& buf, const TileMap<D>& map, const uint16_t* gtile, int gstride, int rows_valid, int tid) {
-  if (rows_valid >= TileMap<D>::ROWS) {
-#pragma unroll
-    for (int it = 0; it < TileMap<D>::ITER; ++it) buf.r[it] = *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const char*>(gtile) + map.goff[it]);
-  } else {
-#pragma unroll
-    for (int it = 0; it < TileMap<D>::ITER; ++it) {
-      const int c = tid + it * TileMap<D>::NT, r = c / TileMap<D>::CPR, cc = c - r * TileMap<D>::CPR;
-      const int rr = r < rows_valid ? r : rows_valid - 1;
-      buf.r[it] = *reinterpret_cast<const u32x4_t*>(gtile + rr * gstride + 8 * cc);
-    }
-  }
-}
-template <int D>
-__device__ __forceinline__ void tile_commit(const TileBuf<D>& buf, const TileMap<D>& map, uint16_t* lds) {
-#pragma unroll
-  for (int it = 0; it < TileMap<D>::ITER; ++it) *reinterpret_cast<u32x4_t*>(lds + map.loff[it]) = buf.r[it];
-}
 
 // ---------------------------------------------------------------------------------------------------
 // Direct global -> LDS tile loads (global_load_lds_dwordx4): lane L of a wave-wide load writes its 16 bytes
@@ -164,8 +109,9 @@ __device__ __forceinline__ void dma_tile_ragged(const DmaMap<D>& map, const uint
   dma_tile<D>(m2, gtile, lds, wave);
 }
 
-// Same as ld_frag_tr but for the k order that the swapped rows and the identity-transposed tiles use:
-// slot e of lane half hh <-> tile row k0 + 8*(e>>2) + 4*hh + (e&3).
+// Transposed operand through the LDS transpose load (ds_read_b64_tr_b16): from a row-major tile T[k][c] (pitch in
+// elements) this lane gets column c0 + li of 8 rows, in the k order that the swapped K rows and the
+// identity-transposed tiles use: slot e of lane half hh <-> tile row k0 + 8*(e>>2) + 4*hh + (e&3).
 __device__ __forceinline__ bf16x8_t ld_frag_tr_perm(const uint16_t* tile, int pitch, int k0, int c0, int lane) {
   const int lam = lane & 15, blk = lane >> 4;
   const uint16_t* p = tile + (k0 + 4 * (blk >> 1) + (lam >> 2)) * pitch + c0 + 16 * (blk & 1) + 4 * (lam & 3);
@@ -247,20 +193,5 @@ __device__ __forceinline__ void acc_combine(const float* buf, float16_t (&acc)[D
       for (int r = 0; r < 4; ++r) acc[dt][4 * g + r] = acc[dt][4 * g + r] * w0 + v[r] * w1;
     }
 }
-
-// store one accumulator set (rows = head-dim columns 32*dt + 8g + 4hh + r of tensor row `row`) as bf16
-template <int DT>
-__device__ __forceinline__ void store_acc_row(uint16_t* row, const float16_t (&acc)[DT], float mul, int hh) {
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      uint2 w;
-      w.x = pack_bf16x2(acc[dt][4 * g + 0] * mul, acc[dt][4 * g + 1] * mul);
-      w.y = pack_bf16x2(acc[dt][4 * g + 2] * mul, acc[dt][4 * g + 3] * mul);
-      *reinterpret_cast<uint2*>(row + 32 * dt + 8 * g + 4 * hh) = w;
-    }
-}
-
 
 }  // namespace sar
