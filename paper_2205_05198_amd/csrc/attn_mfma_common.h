@@ -58,9 +58,10 @@ __device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base, T& t
 // every direct load this wave has issued has landed in LDS
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int D>
+// NW = number of waves that share the loads of a tile (the whole workgroup)
+template <int D, int NW = 4>
 struct DmaMap {
-  static constexpr int ROWS = 64, CPR = D / 8, NL = CPR + 1, PER = (NL + 3) / 4;
+  static constexpr int ROWS = 64, CPR = D / 8, NL = CPR + 1, PER = (NL + NW - 1) / NW;
   static constexpr int TILE = ROWS * (D + 8);  // elements of one LDS tile
   uint32_t goff[PER];                          // byte offset of this lane's chunk from the tile's first row
   bool perm;
@@ -69,7 +70,7 @@ struct DmaMap {
     perm = perm_rows;
 #pragma unroll
     for (int u = 0; u < PER; ++u) {
-      const int L = 64 * (wave + 4 * u) + lane, r0 = (L / NL) & (ROWS - 1), c0 = L - (L / NL) * NL;
+      const int L = 64 * (wave + NW * u) + lane, r0 = (L / NL) & (ROWS - 1), c0 = L - (L / NL) * NL;
       int r = perm_rows ? perm_row(r0) : r0;
       r = r < rows_valid ? r : rows_valid - 1;
       goff[u] = 2u * (uint32_t)(r * gstride + 8 * (c0 < CPR ? c0 : CPR - 1));
@@ -81,32 +82,32 @@ struct DmaMap {
 // dma_one issues round u (0 .. PER-1) of this wave's loads, so that callers can spread them between matrix
 // instructions: the texture path accepts one such load every 16 cycles per CU, and a wave that issues its whole
 // share back to back stalls until they are accepted.
-template <int D>
-__device__ __forceinline__ void dma_one(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, int u) {
-  const int l = wave + 4 * u;
-  if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)  // only the last round can run past the tile
+template <int D, int NW>
+__device__ __forceinline__ void dma_one(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave, int u) {
+  const int l = wave + NW * u;
+  if (u < DmaMap<D, NW>::PER - 1 || l < DmaMap<D, NW>::NL)  // only the last round can run past the tile
     dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l);
 }
-template <int D>
-__device__ __forceinline__ void dma_tile(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave) {
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave) {
 #pragma unroll
-  for (int u = 0; u < DmaMap<D>::PER; ++u) dma_one<D>(map, gtile, lds, wave, u);
+  for (int u = 0; u < DmaMap<D, NW>::PER; ++u) dma_one<D, NW>(map, gtile, lds, wave, u);
 }
-template <int D, typename T>
-__device__ __forceinline__ void dma_tile(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, T& token) {
+template <int D, int NW, typename T>
+__device__ __forceinline__ void dma_tile(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave, T& token) {
 #pragma unroll
-  for (int u = 0; u < DmaMap<D>::PER; ++u) {
-    const int l = wave + 4 * u;
-    if (u < DmaMap<D>::PER - 1 || l < DmaMap<D>::NL)
+  for (int u = 0; u < DmaMap<D, NW>::PER; ++u) {
+    const int l = wave + NW * u;
+    if (u < DmaMap<D, NW>::PER - 1 || l < DmaMap<D, NW>::NL)
       dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l, token);
   }
 }
 // the same for a tile that ends before its 64th row: offsets recomputed with clamped rows
-template <int D>
-__device__ __forceinline__ void dma_tile_ragged(const DmaMap<D>& map, const uint16_t* gtile, uint16_t* lds, int wave, int lane, int gstride, int rows_valid) {
-  DmaMap<D> m2;
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile_ragged(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave, int lane, int gstride, int rows_valid) {
+  DmaMap<D, NW> m2;
   m2.init(wave, lane, gstride, map.perm, rows_valid);
-  dma_tile<D>(m2, gtile, lds, wave);
+  dma_tile<D, NW>(m2, gtile, lds, wave);
 }
 
 // Transposed operand through the LDS transpose load (ds_read_b64_tr_b16): from a row-major tile T[k][c] (pitch in

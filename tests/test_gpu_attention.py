@@ -92,6 +92,19 @@ def test_bf16_matrix_core_path_small(d, s, b, A, p, std, causal):
     _check_bf16_heads("bf16", sh, q, k, v, do, got, range(b * A))
 
 
+@pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1)])
+def test_forward_with_128_row_workgroups(d, s, causal, monkeypatch):
+    """The forward kernel with 128 query rows per workgroup (chosen by the library for long sequences) forced on small
+    ragged shapes: lower and upper row groups end on different tiles under the mask, the last block is partly empty."""
+    from gpu_util import run_attn
+    monkeypatch.setenv("SAR_FWD128", "1")
+    sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=5, causal=causal)
+    q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=17)
+    print(f"fwd128 d={d} s={s} causal={causal}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    _check_bf16_heads("fwd128", sh, q, k, v, do, got, range(2))
+
+
 def test_bf16_generic_path_other_head_dim():
     from gpu_util import run_attn
     sh = oracle.AttnShape(s=72, b=1, a=2, h=2 * 40, p=0.1, seed=3)
