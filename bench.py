@@ -172,6 +172,8 @@ def main():
         "ln_bwd": timed(lambda: sar.ln_bwd(rdesc, dy, x, mean, rstd, gamma, dx, dgamma, dbeta, ws2)),
         "bias_dropout_add": timed(lambda: sar.bias_dropout_add(rdesc, x, bias, resid, out, None)),
     }
+    # context for the small sizes: a plain device copy of one [rows, h] tensor moves the bytes of ln_fwd (read + write)
+    copy_ms = timed(lambda: y.copy_(x))
     dbias = torch.empty(h, dtype=torch.float32, device="cuda")
     ws3 = torch.empty(max(16, sar.bias_dropout_add_bwd_workspace(rdesc)), dtype=torch.uint8, device="cuda")
     extra_ms = {
@@ -249,6 +251,8 @@ def main():
                          "tflops_model_12dTN": 12 * d * T * N / (attn_ms * 1e-3) / 1e12,
                          "tflops_executed_18dTN": 18 * d * T * N / (attn_ms * 1e-3) / 1e12},
         "rows_kernels_ms": rows_ms,
+        "rows_copy_reference": {"ms": copy_ms, "gbs": 2 * rows * h * esz / (copy_ms * 1e-3) / 1e9,
+                                "note": "torch copy of one [rows, h] tensor, timed the same way: what a dependency-free stream of ln_fwd's bytes reaches at this size"},
         "rows_kernels_gbs": {n: bytes_alg[n] / (rows_ms[n] * 1e-3) / 1e9 for n in bytes_alg},
         "rows_kernels_frac_hbm_peak": {n: bytes_alg[n] / (rows_ms[n] * 1e-3) / 1e9 / PEAK_HBM_GBS for n in bytes_alg},
         "next_rows_kernels": {n: {"ms": extra_ms[n], "gbs": extra_bytes[n] / (extra_ms[n] * 1e-3) / 1e9,
