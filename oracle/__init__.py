@@ -225,3 +225,24 @@ def bias_dropout_add_bwd(dout, p: float, seed: int, offset: int, row_offset: int
     lib().orc_bias_dropout_add_bwd(ctypes.c_int64(rows), ctypes.c_int64(h), ctypes.c_int64(row_offset), ctypes.c_float(float(np.float32(p))),
                                    ctypes.c_uint64(seed), ctypes.c_uint64(offset), _dp(dout), _dp(dx), _dp(dresid), _dp(dbias))
     return {"dx": dx, "dresid": dresid, "dbias": dbias}
+
+
+def bias_gelu_fwd(x, bias=None):
+    """y = GeLU(x + bias), exact (erf) form; Section 4.1's MLP non-linearity."""
+    x = _f64(x)
+    bias = _f64(bias) if bias is not None else None
+    rows, h = x.shape
+    y = np.empty_like(x)
+    lib().orc_bias_gelu_fwd(ctypes.c_int64(rows), ctypes.c_int64(h), _dp(x), _dp(bias), _dp(y))
+    return y
+
+
+def bias_gelu_bwd(dy, x, bias=None):
+    """dx = dy GeLU'(x + bias), dbias = column sums of dx."""
+    dy, x = _f64(dy), _f64(x)
+    bias = _f64(bias) if bias is not None else None
+    rows, h = x.shape
+    dx = np.empty_like(x)
+    dbias = np.empty(h, dtype=np.float64)
+    lib().orc_bias_gelu_bwd(ctypes.c_int64(rows), ctypes.c_int64(h), _dp(dy), _dp(x), _dp(bias), _dp(dx), _dp(dbias))
+    return {"dx": dx, "dbias": dbias}

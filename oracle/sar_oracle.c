@@ -382,3 +382,32 @@ void orc_bias_dropout_add_bwd(int64_t rows, int64_t h, int64_t row_offset, float
       dbias[c] += dx[r * h + c];
     }
 }
+
+/* ---------------------------------------------------------------------------------------------------
+ * Bias + GeLU of the MLP block (Section 4.1: "the GeLU non-linearity also needs its input ... for
+ * back-propagation").  The paper names the non-linearity only; the definition taken is the exact one of
+ * Hendrycks & Gimpel, GeLU(z) = z Phi(z) with Phi the standard normal CDF, written with erf:
+ *   y_rc  = z Phi(z),  z = x_rc + bias_c,  Phi(z) = (1 + erf(z / sqrt 2)) / 2
+ *   dx_rc = dy_rc (Phi(z) + z phi(z)),  phi(z) = exp(-z^2 / 2) / sqrt(2 pi);  dbias_c = sum_r dx_rc.
+ * bias may be NULL.
+ * --------------------------------------------------------------------------------------------------- */
+void orc_bias_gelu_fwd(int64_t rows, int64_t h, const double* x, const double* bias, double* y) {
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < h; ++c) {
+      const double z = x[r * h + c] + (bias ? bias[c] : 0.0);
+      y[r * h + c] = z * 0.5 * (1.0 + erf(z / sqrt(2.0)));
+    }
+}
+
+void orc_bias_gelu_bwd(int64_t rows, int64_t h, const double* dy, const double* x, const double* bias, double* dx, double* dbias) {
+  const double inv_sqrt_2pi = 1.0 / sqrt(2.0 * 3.14159265358979323846);
+  for (int64_t c = 0; c < h; ++c) dbias[c] = 0.0;
+  for (int64_t r = 0; r < rows; ++r)
+    for (int64_t c = 0; c < h; ++c) {
+      const double z = x[r * h + c] + (bias ? bias[c] : 0.0);
+      const double Phi = 0.5 * (1.0 + erf(z / sqrt(2.0)));
+      const double phi = exp(-0.5 * z * z) * inv_sqrt_2pi;
+      dx[r * h + c] = dy[r * h + c] * (Phi + z * phi);
+      dbias[c] += dx[r * h + c];
+    }
+}
