@@ -180,7 +180,20 @@ def main():
         "bias_dropout_add_ln_fwd": timed(lambda: sar.bias_dropout_add_ln_fwd(rdesc, x, bias, resid, gamma, beta, out, y, mean, rstd)),
         "bias_dropout_add_bwd": timed(lambda: sar.bias_dropout_add_bwd(rdesc, dy, dx, dbias, ws3)),
     }
-    extra_bytes = {"bias_dropout_add_ln_fwd": rows * h * 4 * esz + 8 * rows + 3 * esz * h,   # read x, resid; write out, y
+    # bias + GeLU of the MLP block on one tensor-parallel rank: s*b rows of 4h/t columns
+    g_rows, g_h = s * b, 4 * w.h // w.t
+    gdesc = sar.RowsDesc.make(g_rows, g_h, dtype=SAR_BF16)
+    gx = torch.randn((g_rows, g_h), device="cuda").to(torch.bfloat16)
+    gdy = torch.randn((g_rows, g_h), device="cuda").to(torch.bfloat16)
+    gb = (0.02 * torch.randn(g_h, device="cuda")).to(torch.bfloat16)
+    gy, gdx = torch.empty_like(gx), torch.empty_like(gx)
+    gdb = torch.empty(g_h, dtype=torch.float32, device="cuda")
+    gws = torch.empty(max(16, sar.bias_gelu_bwd_workspace(gdesc)), dtype=torch.uint8, device="cuda")
+    extra_ms["bias_gelu_fwd"] = timed(lambda: sar.bias_gelu_fwd(gdesc, gx, gb, gy))
+    extra_ms["bias_gelu_bwd"] = timed(lambda: sar.bias_gelu_bwd(gdesc, gdy, gx, gb, gdx, gdb, gws))
+    extra_bytes = {"bias_gelu_fwd": g_rows * g_h * 2 * esz + esz * g_h,                       # read x; write y
+                   "bias_gelu_bwd": g_rows * g_h * 3 * esz + esz * g_h + 4 * g_h,             # read dy, x; write dx, dbias
+                   "bias_dropout_add_ln_fwd": rows * h * 4 * esz + 8 * rows + 3 * esz * h,   # read x, resid; write out, y
                    "bias_dropout_add_bwd": rows * h * 2 * esz + 4 * h}                        # read dout; write dx, dbias
 
     # stored-activation baseline (Section 4.1) for the recompute-vs-stored ratio

@@ -207,6 +207,21 @@ size_t bias_dropout_add_bwd_workspace(const sar_rows_desc* desc);
 sar_status bias_dropout_add_bwd(const sar_rows_desc* desc, const void* dout, void* dx, float* dbias,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * bias_gelu_fwd / bias_gelu_bwd -- the non-linearity of the MLP block with its bias (Section 4.1: the GeLU
+ * keeps its input, 8sbh bytes without tensor parallelism, for the backward).  The paper names the function
+ * only; the exact form is taken: GeLU(z) = z Phi(z), Phi the standard normal CDF.
+ *   x [rows, h] (the first linear layer's output on this rank: rows = s*b, h = 4h/t), bias [h] or NULL : in
+ *   y = GeLU(x + bias) [rows, h] : out (desc->dtype; may alias x only if the caller keeps x elsewhere)
+ *   backward: dy, x, bias as above : in;  dx = dy GeLU'(x + bias) [rows, h] : out (may alias dy);
+ *   dbias [h] : out, float, column sums of dx, or NULL (then no workspace is needed).
+ * Only rows, h and dtype of the descriptor are used.
+ */
+sar_status bias_gelu_fwd(const sar_rows_desc* desc, const void* x, const void* bias, void* y, void* stream);
+size_t bias_gelu_bwd_workspace(const sar_rows_desc* desc);
+sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const void* bias, void* dx, float* dbias,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
 const char* sar_last_error(void);
 

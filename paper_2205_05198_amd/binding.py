@@ -128,6 +128,9 @@ def load_library():
         "bias_dropout_add_ln_fwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "bias_dropout_add_bwd_workspace": (sz, [rd]),
         "bias_dropout_add_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, sz, vp]),
+        "bias_gelu_fwd": (ctypes.c_int, [rd, vp, vp, vp, vp]),
+        "bias_gelu_bwd_workspace": (sz, [rd]),
+        "bias_gelu_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, sz, vp]),
         "sar_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in protos.items():
@@ -141,7 +144,8 @@ EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_recompute"
            "attn_core_bwd_recompute_dkdv", "attn_core_fwd_stored",
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
            "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
-           "bias_dropout_add_bwd_workspace", "bias_dropout_add_bwd", "sar_last_error"]
+           "bias_dropout_add_bwd_workspace", "bias_dropout_add_bwd", "bias_gelu_fwd", "bias_gelu_bwd_workspace", "bias_gelu_bwd",
+           "sar_last_error"]
 
 
 def _ptr(t):
@@ -240,3 +244,16 @@ def bias_dropout_add_bwd_workspace(desc: RowsDesc) -> int:
 def bias_dropout_add_bwd(desc: RowsDesc, dout, dx, dbias=None, workspace=None):
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().bias_dropout_add_bwd(ctypes.byref(desc), _ptr(dout), _ptr(dx), _ptr(dbias), _ptr(workspace), nbytes, _stream()))
+
+
+def bias_gelu_fwd(desc: RowsDesc, x, bias, y):
+    _check(load_library().bias_gelu_fwd(ctypes.byref(desc), _ptr(x), _ptr(bias), _ptr(y), _stream()))
+
+
+def bias_gelu_bwd_workspace(desc: RowsDesc) -> int:
+    return int(load_library().bias_gelu_bwd_workspace(ctypes.byref(desc)))
+
+
+def bias_gelu_bwd(desc: RowsDesc, dy, x, bias, dx, dbias=None, workspace=None):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().bias_gelu_bwd(ctypes.byref(desc), _ptr(dy), _ptr(x), _ptr(bias), _ptr(dx), _ptr(dbias), _ptr(workspace), nbytes, _stream()))

@@ -300,4 +300,36 @@ sar_status bias_dropout_add_bwd(const sar_rows_desc* desc, const void* dout, voi
   return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_dropout_add_bwd launch");
 }
 
+sar_status bias_gelu_fwd(const sar_rows_desc* desc, const void* x, const void* bias, void* y, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!x || !y) return fail(SAR_ERR_NULL, "bias_gelu_fwd: NULL tensor pointer");
+  if (!aligned16(x) || !aligned16(y) || (bias && !aligned16(bias))) return fail(SAR_ERR_ALIGN, "bias_gelu_fwd: pointer not 16-byte aligned");
+  hipError_t e = sar::launch_bias_gelu_fwd(P, desc->dtype == SAR_BF16, x, bias, y, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_gelu_fwd launch");
+}
+
+size_t bias_gelu_bwd_workspace(const sar_rows_desc* desc) {
+  if (check_rows_desc(desc, nullptr) != SAR_OK) return 0;
+  return sar::bda_bwd_workspace_bytes(desc->rows, desc->h);
+}
+
+sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const void* bias, void* dx, float* dbias, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+  sar::RowsParams P;
+  sar_status st = check_rows_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  if (!dy || !x || !dx) return fail(SAR_ERR_NULL, "bias_gelu_bwd: NULL tensor pointer");
+  if (!aligned16(dy) || !aligned16(x) || !aligned16(dx) || (bias && !aligned16(bias)))
+    return fail(SAR_ERR_ALIGN, "bias_gelu_bwd: pointer not 16-byte aligned");
+  if (dbias) {
+    const size_t need = sar::bda_bwd_workspace_bytes(P.rows, P.h);
+    if (need && (!workspace || workspace_bytes < need)) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
+    if (need && !aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
+  }
+  hipError_t e = sar::launch_bias_gelu_bwd(P, desc->dtype == SAR_BF16, dy, x, bias, dx, dbias, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? SAR_OK : hip_fail(e, "bias_gelu_bwd launch");
+}
+
 }  // extern "C"

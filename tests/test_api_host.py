@@ -157,3 +157,22 @@ def test_dropout_add_neighbours_argument_errors(lib):
     assert lib.bias_dropout_add_bwd(ctypes.byref(tall), p[0], p[1], p[2], p[3], need - 1, st) == -6
     wide = sar.RowsDesc.make(256, 20480, p=0.1)   # every slab sees every row: no scratch
     assert lib.bias_dropout_add_bwd_workspace(ctypes.byref(wide)) == 0
+
+
+def test_bias_gelu_argument_errors(lib):
+    p = _fake(8)
+    st = ctypes.c_void_p(0)
+    d = sar.RowsDesc.make(64, 256)
+    assert lib.bias_gelu_fwd(None, p[0], p[1], p[2], st) == -1
+    assert lib.bias_gelu_fwd(ctypes.byref(d), None, p[1], p[2], st) == -1
+    assert lib.bias_gelu_fwd(ctypes.byref(d), p[0], p[1], None, st) == -1
+    assert lib.bias_gelu_fwd(ctypes.byref(d), p[0], ctypes.c_void_p(0x3004), p[2], st) == -4
+    assert lib.bias_gelu_fwd(ctypes.byref(sar.RowsDesc.make(64, 100)), p[0], p[1], p[2], st) == -3
+    assert lib.bias_gelu_bwd(ctypes.byref(d), None, p[1], p[2], p[3], None, None, 0, st) == -1
+    assert lib.bias_gelu_bwd(ctypes.byref(d), p[0], p[1], p[2], None, None, None, 0, st) == -1
+    big = sar.RowsDesc.make(4096, 256)                       # rows split over several slab workgroups: dbias needs the workspace
+    need = lib.bias_gelu_bwd_workspace(ctypes.byref(big))
+    assert need > 0 and need == lib.bias_dropout_add_bwd_workspace(ctypes.byref(big))
+    assert lib.bias_gelu_bwd(ctypes.byref(big), p[0], p[1], p[2], p[3], p[4], p[5], need - 1, st) == -6
+    assert lib.bias_gelu_bwd_workspace(None) == 0
+

@@ -167,3 +167,47 @@ def test_bias_dropout_add_bwd(rows, h, dtype, p):
     sar.bias_dropout_add_bwd(desc, dout, dx2, None, None)
     torch.cuda.synchronize()
     assert torch.equal(dx, dx2)
+
+
+@pytest.mark.parametrize("rows,h,dtype,with_bias", [
+    (128, 128, "f32", True),        # tiny
+    (37, 1032, "bf16", True),       # ragged
+    (5, 8, "f32", False),           # smallest row, no bias
+    (2048, 10240, "bf16", True),    # 530B MLP on one tensor-parallel rank: s*b rows of 4h/t
+    (300, 12800, "bf16", False),    # 1T width, rows split over several slab workgroups
+])
+def test_bias_gelu(rows, h, dtype, with_bias):
+    """bias + GeLU forward and backward (dx, dbias) against the fp64 oracle."""
+    from gpu_util import BAR, DT, dev, err, host
+    rng = np.random.default_rng(7)
+    tdt, code = DT[dtype]
+    rnd = (lambda a: a.astype(np.float32)) if dtype == "f32" else (lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).float().numpy())
+    x, dy = rnd(rng.normal(size=(rows, h)) * 1.5), rnd(rng.normal(size=(rows, h)))
+    bias = rnd(rng.normal(size=h) * 0.5) if with_bias else None
+    print(f"bias_gelu rows={rows} h={h} {dtype} bias={with_bias}", flush=True)
+    desc = sar.RowsDesc.make(rows, h, dtype=code)
+    tx, tdy = dev(x, dtype), dev(dy, dtype)
+    tb = dev(bias, dtype) if with_bias else None
+    y, dx, dx2 = torch.empty_like(tx), torch.empty_like(tx), torch.empty_like(tx)
+    dbias = torch.empty(h, dtype=torch.float32, device="cuda")
+    ws = torch.empty(max(16, sar.bias_gelu_bwd_workspace(desc)), dtype=torch.uint8, device="cuda")
+    sar.bias_gelu_fwd(desc, tx, tb, y)
+    sar.bias_gelu_bwd(desc, tdy, tx, tb, dx, dbias, ws)
+    sar.bias_gelu_bwd(desc, tdy, tx, tb, dx2)          # without dbias: the elementwise kernel
+    torch.cuda.synchronize()
+    ref_y = oracle.bias_gelu_fwd(x, bias)
+    ref = oracle.bias_gelu_bwd(dy, x, bias)
+    # An elementwise map whose output is rounded once: |x - ref|_e <= 2^-9 |ref_e| in bf16.  The max-over-RMS bar of the
+    # other rows kernels cannot hold here at 21 M elements (|y| reaches 8, where half a bf16 unit is 0.03 = 0.035 RMS),
+    # so bf16 is judged elementwise with twice that unit plus a small absolute term; fp32 keeps its bar.
+    def ok(got, want):
+        if dtype == "f32":
+            return err(got, want, dtype) < BAR[dtype]
+        rms = float(np.sqrt(np.mean(want ** 2)))
+        return bool(np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-3 * rms))
+    assert ok(host(y), ref_y)
+    assert ok(host(dx), ref["dx"])
+    assert torch.equal(dx, dx2)
+    # dbias is an fp32 sum of fp32 products on both dtypes
+    assert err(host(dbias), ref["dbias"], "f32") < 1e-4
+
