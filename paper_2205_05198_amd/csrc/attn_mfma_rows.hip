@@ -567,15 +567,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
 bool attn_mfma_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 160; }
 
 // 128-row workgroups pay when there are more of them than CUs (256), so that the heaviest one does not set the pace,
-// and when the head dimension is large (measured: -19 % at s = 4096, -20 % at s = 8192, -21 % without the mask, -14 % for
-// 20 heads, all d = 160; +9 % at d = 96 with 512 workgroups; +14 % at the 16-head s = 2048 shape, 256 workgroups).
+// and at the largest head dimension only (measured at d = 160: -19 % at s = 4096, -20 % at s = 8192, -21 % without the
+// mask, -14 % for 20 heads, -20 % for 32 heads; +14 % at the 16-head s = 2048 shape with its 256 workgroups; at d = 128
+// +4 % and +10 % with 768 and 384 workgroups, at d = 96 +9 % with 512).
 // The environment variable SAR_FWD128 = 0 / 1 forces the choice (tests, measurements).
 static bool fwd_use_128(const AttnParams& P) {
   if (P.s < 128) return false;
   const char* e = getenv("SAR_FWD128");
   if (e && (e[0] == '0' || e[0] == '1')) return e[0] == '1';
   const int64_t wgs = (int64_t)((P.s + 127) / 128) * P.b * P.A;
-  return P.d >= 128 && (P.causal ? wgs > 256 : wgs >= 256);
+  return P.d >= 160 && (P.causal ? wgs > 256 : wgs >= 256);
 }
 
 template <int D>
