@@ -31,19 +31,22 @@ namespace sar {
 static constexpr float kLazyRescale = 60.0f;  // the running reference exponent moves only when the row maximum grew by > 2^60
 
 // ===================================================================================================
-// Forward.  Workgroup = 64 query rows: wave = (rg, ks), rg = 32-row group, ks = which 32 keys of each 64-key
-// tile.  K and V tiles (both with swapped rows) go from global memory straight into LDS, two stages each.
+// Forward.  Workgroup = 32 NRG query rows, 2 NRG waves: wave = (rg, ks), rg = 32-row group, ks = which 32 keys of
+// each 64-key tile.  NRG = 2: 64 rows, one wave per SIMD.  NRG = 4: 128 rows, two waves per SIMD, a K / V tile
+// serves twice the rows (half the tile bytes through the L1 per unit of work); under the causal mask the two lower
+// row groups stop one tile before the two upper ones.
+// K and V tiles (both with swapped rows) go from global memory straight into LDS, two stages each.
 // The score tile runs one step ahead of the rest: step j computes S_{j+1} (matrix core + LDS reads) in the same
-// basic block as the softmax / dropout arithmetic of tile j (vector ALU) and the product P_j V_j, so that the
+// basic block as the softmax / dropout arithmetic of tile j and the product P_j V_j, so that the
 // instruction scheduler can overlap the three.  Everything that needs a branch sits at the ends of a step: the
 // causal mask only exists in the variants of the step that produce the diagonal tile, and the (rare) rescaling
 // of the running maximum for tile j+1 is decided at the end of step j.
 // ===================================================================================================
 // DROP = false is the p = 0 variant: no random numbers are drawn at all.
-template <int D, bool DROP>
-__global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+template <int D, bool DROP, int NRG>
+__global__ __launch_bounds__(128 * NRG) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
-  constexpr int BM = 64, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
+  constexpr int BM = 32 * NRG, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32, NW = 2 * NRG;
   constexpr int TILE = BN * KP;
   __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];
   uint16_t* Kst = smem;             // K tile jt lives in Kst + (jt & 1) * TILE
@@ -54,181 +57,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma_kernel(AttnParams P, const 
   const int rb = nrb - 1 - (int)(blockIdx.x / N);  // heaviest row blocks first
   const int bn = blockIdx.x % N, beta = bn / P.A, n = bn % P.A;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31, hh = lane >> 5;
-  const int rg = wave & 1, ks = wave >> 1;
-  const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
-  const int gstride = (int)P.stride_s;
-  const int iw0 = rb * BM + rg * 32;  // first row of this wave
-  const int i = iw0 + li;
-  const int i_ld = i < P.s ? i : P.s - 1;
-  const int jlim = P.causal ? i : P.s - 1;  // last key row i attends to
-
-  bf16x8_t qf[KC];
-#pragma unroll
-  for (int kc = 0; kc < KC; ++kc) qf[kc] = ld_frag(q + base + (int64_t)i_ld * P.stride_s + 16 * kc + 8 * hh);
-  // These must have arrived before the tile loop: a wait left inside the loop would also wait for the direct
-  // loads in flight there, which the compiler does not know about.
-#pragma unroll
-  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(qf[kc]));
-
-  // Philox call index of (row i, key 0): offset + e/8 with e = ((beta*a + head)*s + i)*s
-  const uint64_t rowG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s + (uint64_t)i_ld) * (uint64_t)(P.s >> 3);
-
-  float16_t oacc[DT];
-#pragma unroll
-  for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[dt][e] = 0.f;
-  float l_run = 0.f;
-  const float sc2 = P.scale * kLog2e;
-
-  const int last_row = min(rb * BM + BM - 1, P.s - 1);
-  const int ntile = P.causal ? last_row / BN + 1 : (P.s + BN - 1) / BN;  // the last tile is the only one that needs a mask
-  DmaMap<D> map;
-  map.init(wave, lane, gstride, true);
-  const uint16_t* kg = k + base;
-  const uint16_t* vg = v + base;
-  auto load_tile = [&](const uint16_t* g, uint16_t* st2, int jt) __attribute__((always_inline)) {
-    const int left = P.s - jt * BN;  // only the last tile of the sequence can end before its 64th row
-    if (left >= BN) dma_tile<D>(map, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, wave);
-    else dma_tile_ragged<D>(map, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, wave, lane, gstride, left);
-  };
-  // S^T tile of this wave's 32 keys of tile jt against its 32 rows; st[8*c + e] is the score of key
-  // jt*64 + 32*ks + 16*c + 8*hh + e.  DIAG: the last tile of the row block: keys beyond jlim (above the diagonal, or past the end) are masked.
-  auto scores = [&](const int jt, auto diag) __attribute__((always_inline)) {
-    const uint16_t* Ks = Kst + (jt & 1) * TILE;
-    float16_t st;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) st[e] = 0.f;
-#pragma unroll
-    for (int kc = 0; kc < KC; ++kc) st = mfma32(ld_frag(Ks + (32 * ks + li) * KP + 16 * kc + 8 * hh), qf[kc], st);
-    if (decltype(diag)::value) {
-      const int j0w = jt * BN + 32 * ks;
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        if (j0w + 16 * (e >> 3) + 8 * hh + (e & 7) > jlim) st[e] = -INFINITY;
-    }
-    return st;
-  };
-  // row maximum of a score tile in the softmax's units (alpha*log2(e)*score; alpha > 0), floored so that a fully
-  // masked tile (the upper wave of the first row group on the diagonal) stays finite
-  auto tile_max = [&](const float16_t& st) __attribute__((always_inline)) {
-    float mt = fmaxf(fmaxf(st[0], st[1]), st[2]);
-#pragma unroll
-    for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, st[e]), st[e + 1]);
-    mt = fmaxf(mt, st[15]);
-    return fmaxf(fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2, -1.0e30f);
-  };
-
-  load_tile(kg, Kst, 0);
-  load_tile(vg, Vst, 0);
-  if (ntile > 1) load_tile(kg, Kst, 1);
-  dma_wait();
-  __syncthreads();
-  float16_t st = ntile == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
-  float m_ref = tile_max(st);
-
-  // One step: tile jt's softmax, dropout and P V, and (NEXT != 0) the scores of tile jt+1; NEXT == 2: that tile is
-  // the diagonal one.
-  auto step = [&](const int jt, auto next) __attribute__((always_inline)) {
-    constexpr int NEXT = decltype(next)::value;
-    dma_wait();       // this wave's loads of K tile jt+1 and V tile jt have landed
-    __syncthreads();  // ... and everybody's; nobody reads K tile jt or V tile jt-1 any more
-    if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
-    if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
-    const uint16_t* Vs = Vst + (jt & 1) * TILE;
-    const int j0w = jt * BN + 32 * ks;
-    float16_t stn;
-    if (NEXT == 1) stn = scores(jt + 1, std::false_type{});
-    if (NEXT == 2) stn = scores(jt + 1, std::true_type{});
-    float psum = 0.f;
-    bf16x8_t pf[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      Philox4 rnd = {0u, 0u, 0u, 0u};
-      if (DROP) rnd = philox_call8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1);
-      float pd[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
-        psum += pe;
-        pd[e] = (!DROP || keep_field(rnd, e, P.thresh)) ? pe : 0.f;
-      }
-      pf[c] = pack8(pd);
-    }
-    l_run += psum;
-    // ---- O^T += V^T P^T ----
-#pragma unroll
-    for (int c = 0; c < 2; ++c)
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) oacc[dt] = mfma32(ld_frag_tr_perm(Vs, KP, 32 * ks + 16 * c, 32 * dt, lane), pf[c], oacc[dt]);
-    if (NEXT != 0) {
-      st = stn;
-      // the running reference exponent only moves when the next tile's maximum exceeds it by more than 2^60
-      const float mt = tile_max(stn);
-      if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale) != 0, 0)) {
-        const float m_new = fmaxf(m_ref, mt);
-        const float corr = __builtin_amdgcn_exp2f(m_ref - m_new);
-        m_ref = m_new;
-        l_run *= corr;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[dt][e] *= corr;
-      }
-    }
-  };
-  {
-    int jt = 0;
-    for (; jt + 2 < ntile; ++jt) step(jt, std::integral_constant<int, 1>{});
-    if (jt + 1 < ntile) step(jt++, std::integral_constant<int, 2>{});
-    step(jt, std::integral_constant<int, 0>{});
-  }
-
-  // ---- merge the two key halves of each row group, then O = O^T^T / ((1-p) l), LSE = m + ln l ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-  __syncthreads();
-  float* mg = reinterpret_cast<float*>(smem) + rg * (64 * (16 * DT + 2));
-  if (ks == 1) {
-    acc_put<DT>(mg, oacc, lane);
-    mg[(16 * DT) * 64 + lane] = m_ref;
-    mg[(16 * DT + 1) * 64 + lane] = l_tot;
-  }
-  __syncthreads();
-  if (ks == 0) {
-    const float m1 = mg[(16 * DT) * 64 + lane], l1 = mg[(16 * DT + 1) * 64 + lane];
-    const float m = fmaxf(m_ref, m1);
-    const float w0 = __builtin_amdgcn_exp2f(m_ref - m), w1 = __builtin_amdgcn_exp2f(m1 - m);
-    const float l = l_tot * w0 + l1 * w1;
-    const float inv = P.keep_scale / l;
-    acc_combine<DT>(mg, oacc, w0, w1, lane);
-    acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, oacc, inv, hh);
-    if (i < P.s && hh == 0) lse[(size_t)bn * P.s + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
-  }
-  __syncthreads();
-  lds_rows_to_global<D>(smem + 2 * TILE, o + base + (int64_t)(rb * BM) * P.stride_s, gstride, P.s - rb * BM, tid);
-}
-
-// ===================================================================================================
-// Forward with 128 query rows per workgroup: 8 waves = 4 row groups x 2 key halves, two waves per SIMD.  The
-// wave code is that of attn_fwd_mfma_kernel; a K / V tile now serves twice the rows (half the tile bytes through
-// the L1 per unit of work) and the two waves of a SIMD fill each other's stalls.  Used when there are enough row
-// blocks to balance them over the CUs (see the launcher).
-// ===================================================================================================
-template <int D, bool DROP>
-__global__ __launch_bounds__(512) void attn_fwd128_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
-                                                           const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
-  constexpr int BM = 128, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32;
-  constexpr int TILE = BN * KP;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[4 * TILE];
-  uint16_t* Kst = smem;             // K tile jt lives in Kst + (jt & 1) * TILE
-  uint16_t* Vst = smem + 2 * TILE;  // V tile jt lives in Vst + (jt & 1) * TILE
-
-  const int N = P.b * P.A;
-  const int nrb = (P.s + BM - 1) / BM;
-  const int rb = nrb - 1 - (int)(blockIdx.x / N);  // heaviest row blocks first
-  const int bn = blockIdx.x % N, beta = bn / P.A, n = bn % P.A;
-  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31, hh = lane >> 5;
-  const int rg = wave & 3, ks = wave >> 2;
+  const int rg = wave % NRG, ks = wave / NRG;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int gstride = (int)P.stride_s;
   const int iw0 = rb * BM + rg * 32;  // first row of this wave
@@ -259,8 +88,8 @@ __global__ __launch_bounds__(512) void attn_fwd128_mfma_kernel(AttnParams P, con
   const int ntile = P.causal ? last_row / BN + 1 : (P.s + BN - 1) / BN;  // tiles the workgroup streams
   // tiles this wave has rows for: the two lower row groups stop one tile before the two upper ones under the causal
   // mask; a wave's last tile is the only one that needs a mask
-  const int nt_w = P.causal ? min(iw0 + 31, P.s - 1) / BN + 1 : ntile;
-  DmaMap<D, 8> map;
+  const int nt_w = (NRG > 2 && P.causal) ? min(iw0 + 31, P.s - 1) / BN + 1 : ntile;
+  DmaMap<D, NW> map;
   map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
   const uint16_t* vg = v + base;
@@ -359,12 +188,13 @@ __global__ __launch_bounds__(512) void attn_fwd128_mfma_kernel(AttnParams P, con
     for (; jt + 2 < nt_w; ++jt) step(jt, std::integral_constant<int, 1>{});
     if (jt + 1 < nt_w) step(jt++, std::integral_constant<int, 2>{});
     step(jt++, std::integral_constant<int, 0>{});
-    for (; jt < ntile; ++jt) {  // a tile above this wave's rows: keep pace with the workgroup's barriers and loads
-      dma_wait();
-      __syncthreads();
-      if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
-      if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
-    }
+    if constexpr (NRG > 2)
+      for (; jt < ntile; ++jt) {  // a tile above this wave's rows: keep pace with the workgroup's barriers and loads
+        dma_wait();
+        __syncthreads();
+        if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
+        if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
+      }
   }
 
   // ---- merge the two key halves of each row group, then O = O^T^T / ((1-p) l), LSE = m + ln l ----
@@ -387,10 +217,14 @@ __global__ __launch_bounds__(512) void attn_fwd128_mfma_kernel(AttnParams P, con
     acc_combine<DT>(mg, oacc, w0, w1, lane);
     if (i < P.s && hh == 0) lse[(size_t)bn * P.s + i] = (m + __builtin_amdgcn_logf(l)) * kLn2;
   }
-  __syncthreads();  // the exchange buffers overlap the two output tiles
-  if (ks == 0) acc_to_lds_rows<DT>(smem + (rg >> 1) * TILE, KP, 32 * (rg & 1) + li, oacc, inv, hh);
-  __syncthreads();
-  {
+  if constexpr (NRG == 2) {  // 64 rows: the output tile sits behind the exchange buffers
+    if (ks == 0) acc_to_lds_rows<DT>(smem + 2 * TILE, KP, 32 * rg + li, oacc, inv, hh);
+    __syncthreads();
+    lds_rows_to_global<D>(smem + 2 * TILE, o + base + (int64_t)(rb * BM) * P.stride_s, gstride, P.s - rb * BM, tid);
+  } else {  // 128 rows: two output tiles that overlap the exchange buffers
+    __syncthreads();
+    if (ks == 0) acc_to_lds_rows<DT>(smem + (rg >> 1) * TILE, KP, 32 * (rg & 1) + li, oacc, inv, hh);
+    __syncthreads();
     const int half = tid >> 8;  // threads 0..255 copy rows 0..63 out, threads 256..511 rows 64..127
     lds_rows_to_global<D>(smem + half * TILE, o + base + (int64_t)(rb * BM + 64 * half) * P.stride_s, gstride, P.s - rb * BM - 64 * half, tid & 255);
   }
@@ -584,19 +418,19 @@ static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const
   if (fwd_use_128(P)) {
     const int N128 = P.b * P.A, nrb128 = (P.s + 127) / 128;
     if (P.thresh != 0)
-      hipLaunchKernelGGL((attn_fwd128_mfma_kernel<D, true>), dim3((unsigned)(nrb128 * N128)), dim3(512), 0, st, P, (const uint16_t*)q,
+      hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 4>), dim3((unsigned)(nrb128 * N128)), dim3(512), 0, st, P, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)o, lse);
     else
-      hipLaunchKernelGGL((attn_fwd128_mfma_kernel<D, false>), dim3((unsigned)(nrb128 * N128)), dim3(512), 0, st, P, (const uint16_t*)q,
+      hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false, 4>), dim3((unsigned)(nrb128 * N128)), dim3(512), 0, st, P, (const uint16_t*)q,
                          (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)o, lse);
     return hipGetLastError();
   }
   const int N = P.b * P.A, nrb = (P.s + 63) / 64;
   if (P.thresh != 0)
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 2>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (uint16_t*)o, lse);
   else  // every element is kept: the variant that draws no random numbers
-    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+    hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false, 2>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (uint16_t*)o, lse);
   return hipGetLastError();
 }
