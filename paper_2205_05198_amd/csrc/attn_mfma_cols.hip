@@ -177,16 +177,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
   }
   // ---- sum the two row halves, scale, store ----
   __syncthreads();
+  // each wave of a pair gives one accumulator set away and finishes the other: the upper half completes dV, the lower dK
   float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
-  if (is == 1) {
-    acc_put<DT>(mg, dkacc, lane);
-    acc_put<DT>(mg + 16 * DT * 64, dvacc, lane);
-  }
+  if (is == 1) acc_put<DT>(mg, dkacc, lane);
+  else acc_put<DT>(mg + 16 * DT * 64, dvacc, lane);
   __syncthreads();
   if (is == 0) {
     acc_combine<DT>(mg, dkacc, 1.f, 1.f, lane);
-    acc_combine<DT>(mg + 16 * DT * 64, dvacc, 1.f, 1.f, lane);
     acc_to_lds_rows<DT>(smem + 4 * TILE, KP, 32 * kgp + li, dkacc, P.scale, hh);
+  } else {
+    acc_combine<DT>(mg + 16 * DT * 64, dvacc, 1.f, 1.f, lane);
     acc_to_lds_rows<DT>(smem + 5 * TILE, KP, 32 * kgp + li, dvacc, 1.0f, hh);
   }
   __syncthreads();
