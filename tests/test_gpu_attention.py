@@ -190,3 +190,34 @@ def test_longer_sequence_single_head():
     print("bf16 s=4096 one head", flush=True)
     got = run_attn(sh, "bf16", q, k, v, do)
     _check_bf16_heads("s4096", sh, q, k, v, do, got, range(1))
+
+
+def test_longer_sequence_single_head_128_row_workgroups(monkeypatch):
+    """The same with the forward's 128-row workgroups (what the library picks at this head dimension once there are more
+    row blocks than CUs): 32 row blocks, up to 64 tiles each."""
+    from gpu_util import run_attn
+    monkeypatch.setenv("SAR_FWD128", "1")
+    s, d = 4096, 160
+    sh = oracle.AttnShape(s=s, b=1, a=8, h=8 * d, t=8, rank=5, p=0.1, seed=1234, offset=99)
+    q, k, v, do = attn_inputs(s, 1, 1, d, "bf16", seed=61)
+    print("bf16 s=4096 one head, 128-row forward", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    _check_bf16_heads("s4096-128", sh, q, k, v, do, got, range(1))
+
+
+def test_stored_baseline_full_size_sampled_head():
+    """The stored-activation baseline at the benchmark's shape (530B shard): mask of one head bit for bit, P and D within one
+    bf16 rounding, outputs and gradients of that head to the bf16 bar."""
+    from gpu_util import run_attn
+    w = WORKLOADS["530B"]
+    sh = oracle.AttnShape(s=w.s, b=w.b, a=w.a, h=w.h, t=w.t, rank=3, p=w.p, seed=w.seed)
+    q, k, v, do = attn_inputs(w.s, w.b, w.A, w.d, "bf16", seed=w.seed)
+    print("stored 530B", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, stored=True)
+    n = 9
+    f = oracle.attn_fwd(sh, q, k, v, materialise=True, heads=(n, n + 1))
+    assert np.array_equal(got["M"][0, n], f["M"][0])
+    for nm in ("P", "D"):
+        assert np.max(np.abs(got[nm][0, n] - f[nm][0])) <= 2.0 ** -8, nm
+    _check_bf16_heads("stored-530B", sh, q, k, v, do, got, (n,))
+
