@@ -13,8 +13,10 @@ namespace sar {
 // tiles are first moved to the one-key-per-lane layout by multiplying with an identity on the matrix core.
 // ===================================================================================================
 // DROP = false is the p = 0 variant: no random numbers are drawn at all.
+// Up to d = 96 two workgroups fit a CU (LDS), if the compiler keeps a wave within half the register file: second
+// argument = waves per SIMD.
 template <int D, bool DROP>
-__global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+__global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v, const float* __restrict__ lse,
                                                                 const uint16_t* __restrict__ dO, const float* __restrict__ delta,
                                                                 uint16_t* __restrict__ dk, uint16_t* __restrict__ dv) {
@@ -55,11 +57,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
       dma_tile_ragged<D>(map, dog + (int64_t)(it0 * BI) * gstride, stages + (it0 & 1) * 2 * TILE + TILE, wave, lane, gstride, leftq);
     }
   }
-  if (tid < BI) {
-    const int ir = min(it0 * BI + tid, P.s - 1);
-    lse_s[it0 & 1][tid] = lse[(size_t)bn * P.s + ir] * kLog2e;
-    delta_s[it0 & 1][tid] = delta[(size_t)bn * P.s + ir];
-  }
+  // Row statistics (LSE, delta) of a query tile travel like the tile itself: wave 0 sends one float per row straight
+  // into LDS.  Through registers, the wait for them would also wait for all of wave 0's tile loads in flight (the
+  // counter is in order), and the other three waves would wait for wave 0 at the next barrier.
+  auto load_stats = [&](int i_first, int stage) __attribute__((always_inline)) {
+    const int ir = min(i_first + lane, P.s - 1);
+    dma4(lse + (size_t)bn * P.s + ir, lds_addr(lse_s[stage]));
+    dma4(delta + (size_t)bn * P.s + ir, lds_addr(delta_s[stage]));
+  };
+  if (wave == 0) load_stats(it0 * BI, it0 & 1);
   // A operands of S^T and dD^T: LDS row 32*kgp + li holds key jw0 + perm_row(li)
   const uint16_t* kw = Ksm + (32 * kgp + li) * KP + 8 * hh;
   const uint16_t* vw = Vsm + (32 * kgp + li) * KP + 8 * hh;
@@ -84,7 +90,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
     const int i0 = it * BI;
     dma_wait();       // this wave's share of tile `it` (and, the first time, of K and V) has landed
     __syncthreads();  // ... and everybody's; nobody reads the other stage any more
-    float lse_n = 0.f, delta_n = 0.f;
     if (it + 1 < nit) {  // next tile's loads fly while this one is computed
       uint16_t* nxt = stages + ((it + 1) & 1) * 2 * TILE;
       const int left = P.s - (i0 + BI);
@@ -95,11 +100,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         dma_tile_ragged<D>(map, qg + (int64_t)(i0 + BI) * gstride, nxt, wave, lane, gstride, left);
         dma_tile_ragged<D>(map, dog + (int64_t)(i0 + BI) * gstride, nxt + TILE, wave, lane, gstride, left);
       }
-      if (tid < BI) {
-        const int ir = min(i0 + BI + tid, P.s - 1);
-        lse_n = lse[(size_t)bn * P.s + ir];
-        delta_n = delta[(size_t)bn * P.s + ir];
-      }
+      if (wave == 0) load_stats(i0 + BI, (it + 1) & 1);
     }
     const uint16_t* Qs = stages + (it & 1) * 2 * TILE;
     const uint16_t* dOs = Qs + TILE;
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
         dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
       }
       const int i = i0w + li;
-      const float lse2 = lse_c[32 * is + li], dl = delta_c[32 * is + li];
+      const float lse2 = lse_c[32 * is + li] * kLog2e, dl = delta_c[32 * is + li];
       const uint64_t rowG = headG + (uint64_t)min(i, P.s - 1) * (uint64_t)(P.s >> 3);
       if (diag || i0w + 31 >= P.s) {  // uniform per wave: keys j > i and rows past the end get probability exp2(-inf) = 0
         asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
@@ -162,10 +163,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_mfma_kernel(AttnParams P, c
           dkacc[dt] = mfma32(ld_frag_tr_perm(Qs, KP, 32 * is + 16 * X, 32 * dt, lane), sT, dkacc[dt]);
         }
       }
-    }
-    if (it + 1 < nit && tid < BI) {  // the other stage's row statistics: last read in the previous step
-      lse_s[(it + 1) & 1][tid] = lse_n * kLog2e;
-      delta_s[(it + 1) & 1][tid] = delta_n;
     }
     // Keep the loop-carried accumulators in the accumulation registers (AGPRs) across the back-edge; without
     // this the compiler copies all of them to VGPRs and back on every trip.

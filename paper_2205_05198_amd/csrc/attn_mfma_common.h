@@ -55,6 +55,10 @@ template <typename T>
 __device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base, T& token) {
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : "+v"(token) : "v"(gaddr), "s"(lds_base) : "m0");
 }
+// 4 bytes per lane: lane L writes at (LDS base) + 4 L (per-row statistics of a tile: one float per row)
+__device__ __forceinline__ void dma4(const void* gaddr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(gaddr), "s"(lds_base) : "m0");
+}
 // every direct load this wave has issued has landed in LDS
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 

@@ -282,7 +282,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_stored_mfma_kernel(AttnPara
   };
   dma_tile<D>(mapv, v + base + (int64_t)(kb * BN) * gstride, Vsm, wave);
   load(it0);
-  if (tid < BI) delta_s[it0 & 1][tid] = delta[(size_t)bn * P.s + it0 * BI + tid];
+  // delta of the tile's rows goes straight into LDS like the tile (a register load would make wave 0 wait for its tile loads)
+  if (wave == 0) dma4(delta + (size_t)bn * P.s + it0 * BI + lane, lds_addr(delta_s[it0 & 1]));
   const uint16_t* vw = Vsm + (32 * kgp + li) * KP + 8 * hh;  // LDS row 32*kgp + li holds key kb*64 + 32*kgp + perm_row(li)
   bf16x8_t ident[2];
 #pragma unroll
@@ -301,10 +302,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_stored_mfma_kernel(AttnPara
   for (int it = it0; it < nit; ++it) {
     dma_wait();
     __syncthreads();
-    float delta_n = 0.f;
     if (it + 1 < nit) {
       load(it + 1);
-      if (tid < BI) delta_n = delta[(size_t)bn * P.s + (it + 1) * BI + tid];
+      if (wave == 0) dma4(delta + (size_t)bn * P.s + (it + 1) * BI + lane, lds_addr(delta_s[(it + 1) & 1]));
     }
     const uint16_t* Qs = stages + (it & 1) * STG;
     const uint16_t* dOs = Qs + TILE;
@@ -350,7 +350,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_stored_mfma_kernel(AttnPara
         dkacc[dt] = mfma32(ld_frag_tr_perm(Qs, KP, 32 * is + 16 * X, 32 * dt, lane), sT, dkacc[dt]);
       }
     }
-    if (it + 1 < nit && tid < BI) delta_s[(it + 1) & 1][tid] = delta_n;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       asm volatile("" : "+a"(dkacc[dt]));
