@@ -15,7 +15,11 @@ namespace sar {
 // DROP = false is the p = 0 variant: no random numbers are drawn at all.
 // Up to d = 96 two workgroups fit a CU (LDS), if the compiler keeps a wave within half the register file: second
 // argument = waves per SIMD.
-template <int D, bool DROP>
+// EVEN: s is a multiple of 64, every query tile is full.  Then the loads of the next (Q, dO) block are dealt out one
+// per pair of score-tile matrix instructions instead of all at the top of the step: the L1 accepts one wave-wide
+// load per 16 cycles per CU, a pair of 32x32x16 instructions keeps a SIMD busy for 64, so four waves that each issue
+// one load per pair never queue behind each other (issued back to back, all four sit through all 44 loads).
+template <int D, bool DROP, bool EVEN>
 __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v, const float* __restrict__ lse,
                                                                 const uint16_t* __restrict__ dO, const float* __restrict__ delta,
@@ -90,8 +94,15 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
     const int i0 = it * BI;
     dma_wait();       // this wave's share of tile `it` (and, the first time, of K and V) has landed
     __syncthreads();  // ... and everybody's; nobody reads the other stage any more
-    if (it + 1 < nit) {  // next tile's loads fly while this one is computed
-      uint16_t* nxt = stages + ((it + 1) & 1) * 2 * TILE;
+    // EVEN: the first round of the next block's loads; the last step fetches its own block again (into the stage
+    // that nobody reads any more) so that the step has one path
+    const int inx = min(it + 1, nit - 1) * BI;
+    uint16_t* nxt = stages + ((it + 1) & 1) * 2 * TILE;
+    if constexpr (EVEN) {
+      dma_one<D>(map, qg + (int64_t)inx * gstride, nxt, wave, 0);
+      dma_one<D>(map, dog + (int64_t)inx * gstride, nxt + TILE, wave, 0);
+      if (wave == 0) load_stats(inx, (it + 1) & 1);
+    } else if (it + 1 < nit) {  // next tile's loads fly while this one is computed
       const int left = P.s - (i0 + BI);
       if (left >= BI) {
         dma_tile<D>(map, qg + (int64_t)(i0 + BI) * gstride, nxt, wave);
@@ -107,15 +118,37 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
     const float* lse_c = lse_s[it & 1];
     const float* delta_c = delta_s[it & 1];
     const int i0w = i0 + 32 * is;  // this wave's 32 rows
-    if (!P.causal || i0w + 31 >= jw0) {  // otherwise every row precedes this wave's keys
+    // i0w + 31 < jw0 (the upper right quarter of the diagonal tile): every row precedes this wave's keys.  EVEN: the
+    // wave runs the tile fully masked rather than skipping it (its share of the loads sits inside)
+    if (EVEN || !P.causal || i0w + 31 >= jw0) {
       const bool diag = P.causal && (i0w < jw0 + 31);
       float16_t st, dd;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
+      if constexpr (EVEN) {  // loads between the matrix instructions: keep the accumulators where they are around them
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          asm volatile("" : "+a"(dkacc[dt]));
+          asm volatile("" : "+a"(dvacc[dt]));
+        }
+      }
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
         st = mfma32(ld_frag(kw + 16 * kc), ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
         dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
+        if constexpr (EVEN) {  // rounds 1 .. PER-1 of the Q tile, then of the dO tile
+          constexpr int PER = DmaMap<D>::PER;
+          static_assert(2 * (PER - 1) <= KC, "more load rounds than pairs of matrix instructions");
+          if (1 + kc < PER) dma_one<D>(map, qg + (int64_t)inx * gstride, nxt, wave, 1 + kc);
+          else if (2 + kc - PER < PER) dma_one<D>(map, dog + (int64_t)inx * gstride, nxt + TILE, wave, 2 + kc - PER);
+        }
+      }
+      if constexpr (EVEN) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          asm volatile("" : "+a"(dkacc[dt]));
+          asm volatile("" : "+a"(dvacc[dt]));
+        }
       }
       const int i = i0w + li;
       const float lse2 = lse_c[32 * is + li] * kLog2e, dl = delta_c[32 * is + li];
@@ -173,6 +206,7 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
     }
   }
   // ---- sum the two row halves, scale, store ----
+  dma_wait();  // EVEN: the last step's loads still target the stages that the exchange buffers overlap
   __syncthreads();
   // each wave of a pair gives one accumulator set away and finishes the other: the upper half completes dV, the lower dK
   float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
@@ -195,12 +229,21 @@ template <int D>
 static hipError_t bwd_dkdv_d(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO, const float* delta,
                              void* dk, void* dv, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
-  if (P.thresh != 0)
-    hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D, true>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
-                       (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
-  else
-    hipLaunchKernelGGL((attn_bwd_dkdv_mfma_kernel<D, false>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
-                       (const uint16_t*)v, lse, (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse,
+                       (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+  };
+  // interleaved loads pay at d = 160 only (530B shard -3 %, 1T -6 %, s = 4096 -3 %; d = 128 unchanged; d = 96, where two
+  // workgroups share a CU and fill each other's stalls anyway, +2 %)
+  constexpr bool kInterleave = D >= 160;
+  const bool even = kInterleave && P.s % 64 == 0;
+  if (P.thresh != 0) {
+    if (even) go(attn_bwd_dkdv_mfma_kernel<D, true, kInterleave>);
+    else go(attn_bwd_dkdv_mfma_kernel<D, true, false>);
+  } else {
+    if (even) go(attn_bwd_dkdv_mfma_kernel<D, false, kInterleave>);
+    else go(attn_bwd_dkdv_mfma_kernel<D, false, false>);
+  }
   return hipGetLastError();
 }
 
