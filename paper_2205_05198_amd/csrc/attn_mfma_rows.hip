@@ -43,8 +43,12 @@ static constexpr float kLazyRescale = 60.0f;  // the running reference exponent 
 // of the running maximum for tile j+1 is decided at the end of step j.
 // ===================================================================================================
 // DROP = false is the p = 0 variant: no random numbers are drawn at all.
-template <int D, bool DROP, int NRG>
-__global__ __launch_bounds__(128 * NRG) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+// LW (64-row workgroups only): four more waves, one per SIMD, that do nothing but fetch the K / V tiles.  A wave-wide
+// 16-byte load occupies its wave for about 64 cycles (16 bytes per cycle per SIMD; four SIMDs are the CU's 64 B/clk), so
+// 42 loads per step cost each computing wave some 650 cycles of a 2200-cycle step; in a wave of their own those cycles
+// run beside the arithmetic of the SIMD's other wave.  The price: every wave must fit half the register file.
+template <int D, bool DROP, int NRG, bool LW = false>
+__global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                            const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse) {
   constexpr int BM = 32 * NRG, BN = 64, KP = D + 8, KC = D / 16, DT = D / 32, NW = 2 * NRG;
   constexpr int TILE = BN * KP;
@@ -60,6 +64,36 @@ __global__ __launch_bounds__(128 * NRG) void attn_fwd_mfma_kernel(AttnParams P, 
   const int rg = wave % NRG, ks = wave / NRG;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int gstride = (int)P.stride_s;
+  if constexpr (LW) {
+    static_assert(NRG == 2, "the loader wave goes with 64-row workgroups");
+    if (wave >= NW) {  // a loader (one per SIMD): same barriers as the others
+      const int lw = wave - NW;
+      const int last_row_l = min(rb * BM + BM - 1, P.s - 1);
+      const int nt = P.causal ? last_row_l / BN + 1 : (P.s + BN - 1) / BN;
+      DmaMap<D, 4> lmap;
+      lmap.init(lw, lane, gstride, true);
+      auto fetch = [&](const uint16_t* g, uint16_t* st2, int jt) __attribute__((always_inline)) {
+        const int left = P.s - jt * BN;
+        if (left >= BN) dma_tile<D>(lmap, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, lw);
+        else dma_tile_ragged<D>(lmap, g + (int64_t)(jt * BN) * gstride, st2 + (jt & 1) * TILE, lw, lane, gstride, left);
+      };
+      fetch(k + base, Kst, 0);
+      fetch(v + base, Vst, 0);
+      if (nt > 1) fetch(k + base, Kst, 1);
+      dma_wait();
+      __syncthreads();  // tiles K 0, V 0, K 1 are there
+      for (int jt = 0; jt < nt; ++jt) {
+        __syncthreads();  // top of step jt: K tile jt and V tile jt-1 are free
+        if (jt + 2 < nt) fetch(k + base, Kst, jt + 2);
+        if (jt + 1 < nt) fetch(v + base, Vst, jt + 1);
+        dma_wait();
+      }
+      __syncthreads();  // the three barriers of the others' epilogue
+      __syncthreads();
+      __syncthreads();
+      return;
+    }
+  }
   const int iw0 = rb * BM + rg * 32;  // first row of this wave
   const int i = iw0 + li;
   const int i_ld = i < P.s ? i : P.s - 1;
@@ -125,10 +159,12 @@ __global__ __launch_bounds__(128 * NRG) void attn_fwd_mfma_kernel(AttnParams P, 
     return fmaxf(fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2, -1.0e30f);
   };
 
-  load_tile(kg, Kst, 0);
-  load_tile(vg, Vst, 0);
-  if (ntile > 1) load_tile(kg, Kst, 1);
-  dma_wait();
+  if constexpr (!LW) {
+    load_tile(kg, Kst, 0);
+    load_tile(vg, Vst, 0);
+    if (ntile > 1) load_tile(kg, Kst, 1);
+    dma_wait();
+  }
   __syncthreads();
   float16_t st = nt_w == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
   float m_ref = tile_max(st);
@@ -137,10 +173,12 @@ __global__ __launch_bounds__(128 * NRG) void attn_fwd_mfma_kernel(AttnParams P, 
   // the diagonal one.
   auto step = [&](const int jt, auto next) __attribute__((always_inline)) {
     constexpr int NEXT = decltype(next)::value;
-    dma_wait();       // this wave's loads of K tile jt+1 and V tile jt have landed
-    __syncthreads();  // ... and everybody's; nobody reads K tile jt or V tile jt-1 any more
-    if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
-    if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
+    if constexpr (!LW) dma_wait();  // this wave's loads of K tile jt+1 and V tile jt have landed
+    __syncthreads();                // ... and everybody's; nobody reads K tile jt or V tile jt-1 any more
+    if constexpr (!LW) {
+      if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
+      if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
+    }
     const uint16_t* Vs = Vst + (jt & 1) * TILE;
     const int j0w = jt * BN + 32 * ks;
     float16_t stn;
@@ -426,6 +464,21 @@ static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const
     return hipGetLastError();
   }
   const int N = P.b * P.A, nrb = (P.s + 63) / 64;
+  {
+    // loader waves: measured -10 % at d = 160 (530B shard), -9 % at d = 128 (175B), -8 % at d = 64, +15 % at d = 96 (22B
+    // shard: three 4-wave workgroups share a CU there and fill each other's stalls).  SAR_FWDLW = 0 / 1 forces the choice.
+    const char* lw = getenv("SAR_FWDLW");
+    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D != 96;
+    if (use_lw) {
+      if (P.thresh != 0)
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 2, true>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q,
+                           (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)o, lse);
+      else
+        hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, false, 2, true>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q,
+                           (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)o, lse);
+      return hipGetLastError();
+    }
+  }
   if (P.thresh != 0)
     hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 2>), dim3((unsigned)(nrb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (uint16_t*)o, lse);
