@@ -273,8 +273,9 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
 // P_ij = exp(alpha q_i.k_j - LSE_i), dP = (dO V^T) o M/(1-p), dS = P o (dP - delta) recomputed per tile.
 // Same workgroup shape as the forward.
 // ===================================================================================================
-template <int D, bool DROP>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+// LW: four more waves that fetch the tiles, as in the forward.
+template <int D, bool DROP, bool LW = false>
+__global__ __launch_bounds__(LW ? 512 : 256) void attn_bwd_dq_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                               const uint16_t* __restrict__ v, const uint16_t* __restrict__ o,
                                                               const float* __restrict__ lse, const uint16_t* __restrict__ dO,
                                                               uint16_t* __restrict__ dq, float* __restrict__ delta) {
@@ -290,6 +291,36 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
   const int rg = wave & 1, ks = wave >> 1;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int gstride = (int)P.stride_s;
+  if constexpr (LW) {
+    if (wave >= 4) {  // a loader (one per SIMD): same barriers as the others
+      const int lw = wave - 4;
+      const int last_row_l = min(rb * BM + BM - 1, P.s - 1);
+      const int nt = P.causal ? last_row_l / BN + 1 : (P.s + BN - 1) / BN;
+      DmaMap<D> lmap;
+      lmap.init(lw, lane, gstride, true);
+      auto fetch = [&](int jt) __attribute__((always_inline)) {
+        uint16_t* st2 = smem + (jt & 1) * 2 * TILE;
+        const int left = P.s - jt * BN;
+        if (left >= BN) {
+          dma_tile<D>(lmap, k + base + (int64_t)(jt * BN) * gstride, st2, lw);
+          dma_tile<D>(lmap, v + base + (int64_t)(jt * BN) * gstride, st2 + TILE, lw);
+        } else {
+          dma_tile_ragged<D>(lmap, k + base + (int64_t)(jt * BN) * gstride, st2, lw, lane, gstride, left);
+          dma_tile_ragged<D>(lmap, v + base + (int64_t)(jt * BN) * gstride, st2 + TILE, lw, lane, gstride, left);
+        }
+      };
+      fetch(0);
+      for (int jt = 0; jt < nt; ++jt) {
+        dma_wait();
+        __syncthreads();  // top of step jt: tile jt is there, the other stage is free
+        if (jt + 1 < nt) fetch(jt + 1);
+      }
+      __syncthreads();  // the three barriers of the others' epilogue
+      __syncthreads();
+      __syncthreads();
+      return;
+    }
+  }
   const int iw0 = rb * BM + rg * 32;
   const int i = iw0 + li;
   const int i_ld = i < P.s ? i : P.s - 1;
@@ -327,20 +358,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma_kernel(AttnParams P, con
   map.init(wave, lane, gstride, true);
   const uint16_t* kg = k + base;
   const uint16_t* vg = v + base;
-  if (P.s >= BN) {
-    dma_tile<D>(map, kg, smem, wave);
-    dma_tile<D>(map, vg, smem + TILE, wave);
-  } else {
-    dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
-    dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
+  if constexpr (!LW) {
+    if (P.s >= BN) {
+      dma_tile<D>(map, kg, smem, wave);
+      dma_tile<D>(map, vg, smem + TILE, wave);
+    } else {
+      dma_tile_ragged<D>(map, kg, smem, wave, lane, gstride, P.s);
+      dma_tile_ragged<D>(map, vg, smem + TILE, wave, lane, gstride, P.s);
+    }
   }
   // One tile step.  MODE says how tile jt+1 is loaded into the other stage meanwhile: 0 = there is none,
   // 1 = loads spread between the matrix instructions below, 2 = the next tile ends before its 64th row: loads with
   // clamped rows, all issued up front.
   auto step = [&](const int jt, auto mode) __attribute__((always_inline)) {
-    constexpr int MODE = decltype(mode)::value;
+    constexpr int MODE = LW ? 0 : decltype(mode)::value;  // with loader waves the computing waves fetch nothing
     const int j0 = jt * BN;
-    dma_wait();       // this wave's share of tile jt has landed
+    if constexpr (!LW) dma_wait();  // this wave's share of tile jt has landed
     __syncthreads();  // ... and everybody's; nobody reads the other stage any more
     uint16_t* nxt = smem + ((jt + 1) & 1) * 2 * TILE;
     const uint16_t* kn = kg + (int64_t)(j0 + BN) * gstride;
@@ -502,6 +535,21 @@ template <int D>
 static hipError_t bwd_dq_d(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dO, void* dq,
                            float* delta, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
+  {
+    // loader waves pay at d = 128 only (175B shard -11 %): at d = 160 they need 232 registers instead of 288 and gain
+    // nothing, at d = 64 / 96 several workgroups share a CU anyway (+5 %, +15 %).  SAR_DQLW = 0 / 1 forces the choice.
+    const char* lw = getenv("SAR_DQLW");
+    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D == 128;
+    if (use_lw) {
+      if (P.thresh != 0)
+        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true, true>), dim3((unsigned)(nb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);
+      else
+        hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, false, true>), dim3((unsigned)(nb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);
+      return hipGetLastError();
+    }
+  }
   if (P.thresh != 0)
     hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true>), dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)o, lse, (const uint16_t*)dO, (uint16_t*)dq, delta);

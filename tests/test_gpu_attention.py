@@ -108,10 +108,11 @@ def test_forward_with_128_row_workgroups(d, s, causal, monkeypatch):
 @pytest.mark.parametrize("lw", ["0", "1"])
 @pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (96, 200, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1)])
 def test_forward_with_and_without_loader_waves(d, s, causal, lw, monkeypatch):
-    """The 64-row forward kernel with (8 waves) and without (4 waves) its tile-fetching waves, both forced whatever the
-    library would pick for the head dimension, on ragged shapes (the last tile is fetched with clamped rows)."""
+    """The 64-row forward kernel and the dQ pass with (8 waves) and without (4 waves) their tile-fetching waves, both forced
+    whatever the library would pick for the head dimension, on ragged shapes (the last tile is fetched with clamped rows)."""
     from gpu_util import run_attn
     monkeypatch.setenv("SAR_FWDLW", lw)
+    monkeypatch.setenv("SAR_DQLW", lw)
     monkeypatch.setenv("SAR_FWD128", "0")
     sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=5, causal=causal)
     q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=19)
