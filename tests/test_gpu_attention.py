@@ -121,6 +121,18 @@ def test_forward_with_and_without_loader_waves(d, s, causal, lw, monkeypatch):
     _check_bf16_heads("fwd-lw" + lw, sh, q, k, v, do, got, range(2))
 
 
+@pytest.mark.parametrize("d,s,causal", [(160, 8, 1), (64, 24, 1), (128, 64, 1), (160, 72, 1), (96, 40, 0), (160, 56, 0)])
+def test_bf16_matrix_core_path_short_sequences(d, s, causal):
+    """Sequences of at most one or two tiles on the matrix-core kernels: the only tile is ragged (rows past the end are
+    fetched clamped and masked), a workgroup has a single step, three of four waves may have nothing but masked keys."""
+    from gpu_util import run_attn
+    sh = oracle.AttnShape(s=s, b=2, a=2, h=2 * d, p=0.1, seed=9, causal=causal)
+    q, k, v, do = attn_inputs(s, 2, 2, d, "bf16", seed=23)
+    print(f"short d={d} s={s} causal={causal}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    _check_bf16_heads("short", sh, q, k, v, do, got, range(4))
+
+
 def test_bf16_generic_path_other_head_dim():
     from gpu_util import run_attn
     sh = oracle.AttnShape(s=72, b=1, a=2, h=2 * 40, p=0.1, seed=3)
