@@ -312,7 +312,7 @@ sar_status bias_gelu_fwd(const sar_rows_desc* desc, const void* x, const void* b
 
 size_t bias_gelu_bwd_workspace(const sar_rows_desc* desc) {
   if (check_rows_desc(desc, nullptr) != SAR_OK) return 0;
-  return sar::bda_bwd_workspace_bytes(desc->rows, desc->h);
+  return sar::bias_gelu_bwd_workspace_bytes(desc->rows, desc->h);
 }
 
 sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const void* bias, void* dx, float* dbias, void* workspace,
@@ -324,7 +324,7 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
   if (!aligned16(dy) || !aligned16(x) || !aligned16(dx) || (bias && !aligned16(bias)))
     return fail(SAR_ERR_ALIGN, "bias_gelu_bwd: pointer not 16-byte aligned");
   if (dbias) {
-    const size_t need = sar::bda_bwd_workspace_bytes(P.rows, P.h);
+    const size_t need = sar::bias_gelu_bwd_workspace_bytes(P.rows, P.h);
     if (need && (!workspace || workspace_bytes < need)) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
     if (need && !aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
   }

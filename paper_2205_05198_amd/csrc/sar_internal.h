@@ -64,7 +64,8 @@ hipError_t launch_bias_dropout_add_ln_fwd(const RowsParams& P, bool bf16, const 
                                           const void* beta, void* out, void* y, float* mean, float* rstd, hipStream_t st);
 size_t bda_bwd_workspace_bytes(int64_t rows, int64_t h);
 hipError_t launch_bias_dropout_add_bwd(const RowsParams& P, bool bf16, const void* dout, void* dx, float* dbias, void* ws, hipStream_t st);
-// bias + GeLU (the MLP block's non-linearity); the backward's workspace is bda_bwd_workspace_bytes
+// bias + GeLU (the MLP block's non-linearity)
+size_t bias_gelu_bwd_workspace_bytes(int64_t rows, int64_t h);
 hipError_t launch_bias_gelu_fwd(const RowsParams& P, bool bf16, const void* x, const void* bias, void* y, hipStream_t st);
 hipError_t launch_bias_gelu_bwd(const RowsParams& P, bool bf16, const void* dy, const void* x, const void* bias, void* dx, float* dbias, void* ws,
                                 hipStream_t st);
