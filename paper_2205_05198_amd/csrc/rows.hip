@@ -402,7 +402,7 @@ __global__ void bda_bwd_finish_kernel(const float* __restrict__ part, int nsplit
 // vector instructions and made both kernels ALU-bound.)
 __device__ __forceinline__ void gelu_parts(float z, float& Phi, float& pdf) {
   const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __frcp_rn(fmaf(0.3275911f, x, 1.f));
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.f));  // 1 ulp; a correctly rounded reciprocal costs ten more instructions
   const float e = __expf(-x * x);
   const float poly = t * fmaf(t, fmaf(t, fmaf(t, fmaf(t, 1.061405429f, -1.453152027f), 1.421413741f), -0.284496736f), 0.254829592f);
   const float erfa = fmaf(-poly, e, 1.f);
@@ -420,66 +420,37 @@ __device__ __forceinline__ float gelu_grad(float z) {
   return fmaf(z, pdf, Phi);
 }
 
-// kGeluU chunks of 8 elements per thread (a workgroup's chunks contiguous per round, all loads issued before the arithmetic)
-constexpr int kGeluU = 1;  // 4 measured slower (29 vs 23 us forward at 2048 x 10240)
-
+// One chunk of 8 elements per thread; grid = (rows, chunks of a row / 256): no index division in the kernel (it cost
+// four instructions per element of a kernel that is bound by its vector arithmetic).  More chunks per thread were slower.
 template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void bias_gelu_fwd_kernel(RowsParams P, const T* __restrict__ x, const T* __restrict__ bias, T* __restrict__ y) {
-  const int64_t nchunk_row = P.h >> 3, total = P.rows * nchunk_row;
-  const int64_t first = (int64_t)blockIdx.x * (256 * kGeluU) + threadIdx.x;
-  float xv[kGeluU][8], bv[kGeluU][8];
+  const int64_t c = ((int64_t)blockIdx.y * 256 + threadIdx.x) << 3;
+  if (c >= P.h) return;
+  const int64_t at = (int64_t)blockIdx.x * P.h + c;
+  float xv[8], bv[8], o[8];
+  Vec8<T>::load(x + at, xv);
+  if (HAS_BIAS) Vec8<T>::load(bias + c, bv);
 #pragma unroll
-  for (int u = 0; u < kGeluU; ++u) {
-    const int64_t idx = first + 256 * u;
-    if (idx < total) {
-      const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
-      Vec8<T>::load(x + r * P.h + c, xv[u]);
-      if (HAS_BIAS) Vec8<T>::load(bias + c, bv[u]);
-    }
+  for (int q = 0; q < 8; ++q) {
+    const float z = HAS_BIAS ? xv[q] + bv[q] : xv[q];
+    o[q] = z * gelu_phi_cdf(z);
   }
-#pragma unroll
-  for (int u = 0; u < kGeluU; ++u) {
-    const int64_t idx = first + 256 * u;
-    if (idx < total) {
-      const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
-      float o[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) {
-        const float z = HAS_BIAS ? xv[u][q] + bv[u][q] : xv[u][q];
-        o[q] = z * gelu_phi_cdf(z);
-      }
-      Vec8<T>::store(y + r * P.h + c, o);
-    }
-  }
+  Vec8<T>::store(y + at, o);
 }
 
 template <typename T, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void bias_gelu_bwd_kernel(RowsParams P, const T* __restrict__ dy, const T* __restrict__ x,
                                                            const T* __restrict__ bias, T* __restrict__ dx) {
-  const int64_t nchunk_row = P.h >> 3, total = P.rows * nchunk_row;
-  const int64_t first = (int64_t)blockIdx.x * (256 * kGeluU) + threadIdx.x;
-  float xv[kGeluU][8], dv[kGeluU][8], bv[kGeluU][8];
+  const int64_t c = ((int64_t)blockIdx.y * 256 + threadIdx.x) << 3;
+  if (c >= P.h) return;
+  const int64_t at = (int64_t)blockIdx.x * P.h + c;
+  float xv[8], dv[8], bv[8], o[8];
+  Vec8<T>::load(x + at, xv);
+  Vec8<T>::load(dy + at, dv);
+  if (HAS_BIAS) Vec8<T>::load(bias + c, bv);
 #pragma unroll
-  for (int u = 0; u < kGeluU; ++u) {
-    const int64_t idx = first + 256 * u;
-    if (idx < total) {
-      const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
-      Vec8<T>::load(x + r * P.h + c, xv[u]);
-      Vec8<T>::load(dy + r * P.h + c, dv[u]);
-      if (HAS_BIAS) Vec8<T>::load(bias + c, bv[u]);
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < kGeluU; ++u) {
-    const int64_t idx = first + 256 * u;
-    if (idx < total) {
-      const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
-      float o[8];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) o[q] = dv[u][q] * gelu_grad(HAS_BIAS ? xv[u][q] + bv[u][q] : xv[u][q]);
-      Vec8<T>::store(dx + r * P.h + c, o);
-    }
-  }
+  for (int q = 0; q < 8; ++q) o[q] = dv[q] * gelu_grad(HAS_BIAS ? xv[q] + bv[q] : xv[q]);
+  Vec8<T>::store(dx + at, o);
 }
 
 // with dbias: a workgroup owns 64 columns and a range of rows, as bda_bwd_slab_kernel
@@ -692,8 +663,7 @@ hipError_t launch_bias_dropout_add_bwd(const RowsParams& P, bool bf16, const voi
 
 template <typename T>
 static hipError_t bias_gelu_fwd_t(const RowsParams& P, const void* x, const void* bias, void* y, hipStream_t st) {
-  const int64_t total = P.rows * (P.h >> 3);
-  dim3 grid((unsigned)((total + 256 * kGeluU - 1) / (256 * kGeluU))), block(256);
+  dim3 grid((unsigned)P.rows, (unsigned)(((P.h >> 3) + 255) / 256)), block(256);
   if (bias) hipLaunchKernelGGL((bias_gelu_fwd_kernel<T, true>), grid, block, 0, st, P, (const T*)x, (const T*)bias, (T*)y);
   else hipLaunchKernelGGL((bias_gelu_fwd_kernel<T, false>), grid, block, 0, st, P, (const T*)x, (const T*)bias, (T*)y);
   return hipGetLastError();
@@ -707,8 +677,7 @@ template <typename T>
 static hipError_t bias_gelu_bwd_t(const RowsParams& P, const void* dy, const void* x, const void* bias, void* dx, float* dbias, void* ws,
                                   hipStream_t st) {
   if (!dbias) {
-    const int64_t total = P.rows * (P.h >> 3);
-    dim3 grid((unsigned)((total + 256 * kGeluU - 1) / (256 * kGeluU))), block(256);
+    dim3 grid((unsigned)P.rows, (unsigned)(((P.h >> 3) + 255) / 256)), block(256);
     if (bias) hipLaunchKernelGGL((bias_gelu_bwd_kernel<T, true>), grid, block, 0, st, P, (const T*)dy, (const T*)x, (const T*)bias, (T*)dx);
     else hipLaunchKernelGGL((bias_gelu_bwd_kernel<T, false>), grid, block, 0, st, P, (const T*)dy, (const T*)x, (const T*)bias, (T*)dx);
     return hipGetLastError();
