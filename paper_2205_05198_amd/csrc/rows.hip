@@ -224,11 +224,8 @@ __global__ void ln_bwd_finish_kernel(const float* __restrict__ part, int nsplit,
 template <typename T, bool HAS_BIAS, bool HAS_MASK>
 __global__ __launch_bounds__(256) void bias_dropout_add_kernel(RowsParams P, const T* __restrict__ x, const T* __restrict__ bias, const T* resid,
                                                               T* out, uint8_t* __restrict__ mask) {
-  const int64_t nchunk_row = P.h >> 3;
-  const int64_t total = P.rows * nchunk_row;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
+  const int64_t r = blockIdx.x, c = ((int64_t)blockIdx.y * 256 + threadIdx.x) << 3;  // grid = (rows, chunks of a row / 256): no index division
+  if (c >= P.h) return;
   float xv[8], rv[8], bv[8], o[8];
   Vec8<T>::load(x + r * P.h + c, xv);
   Vec8<T>::load(resid + r * P.h + c, rv);
@@ -329,11 +326,8 @@ __global__ __launch_bounds__(1024) void bda_ln_fwd_kernel(RowsParams P, const T*
 // ---------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void bda_bwd_kernel(RowsParams P, const T* __restrict__ dout, T* __restrict__ dx) {
-  const int64_t nchunk_row = P.h >> 3;
-  const int64_t total = P.rows * nchunk_row;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int64_t r = idx / nchunk_row, c = (idx - r * nchunk_row) << 3;
+  const int64_t r = blockIdx.x, c = ((int64_t)blockIdx.y * 256 + threadIdx.x) << 3;  // grid = (rows, chunks of a row / 256): no index division
+  if (c >= P.h) return;
   float dv[8], o[8];
   Vec8<T>::load(dout + r * P.h + c, dv);
   const uint64_t e = (uint64_t)(P.row_offset + r) * (uint64_t)P.h + (uint64_t)c;
@@ -578,8 +572,7 @@ hipError_t launch_ln_bwd(const RowsParams& P, bool bf16, const void* dy, const v
 
 template <typename T>
 static hipError_t bda_t(const RowsParams& P, const void* x, const void* bias, const void* resid, void* out, uint8_t* mask, hipStream_t st) {
-  const int64_t total = P.rows * (P.h >> 3);
-  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  dim3 grid((unsigned)P.rows, (unsigned)(((P.h >> 3) + 255) / 256)), block(256);
 #define SAR_BDA(B, M) hipLaunchKernelGGL((bias_dropout_add_kernel<T, B, M>), grid, block, 0, st, P, (const T*)x, (const T*)bias, (const T*)resid, (T*)out, mask)
   if (bias && mask) SAR_BDA(true, true);
   else if (bias) SAR_BDA(true, false);
@@ -639,8 +632,7 @@ size_t bda_bwd_workspace_bytes(int64_t rows, int64_t h) {
 template <typename T>
 static hipError_t bda_bwd_t(const RowsParams& P, const void* dout, void* dx, float* dbias, void* ws, hipStream_t st) {
   if (!dbias) {
-    const int64_t total = P.rows * (P.h >> 3);
-    hipLaunchKernelGGL((bda_bwd_kernel<T>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, P, (const T*)dout, (T*)dx);
+    hipLaunchKernelGGL((bda_bwd_kernel<T>), dim3((unsigned)P.rows, (unsigned)(((P.h >> 3) + 255) / 256)), dim3(256), 0, st, P, (const T*)dout, (T*)dx);
     return hipGetLastError();
   }
   int nslab, nsplit, rps;
