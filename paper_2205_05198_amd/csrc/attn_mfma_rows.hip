@@ -273,7 +273,9 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
 // P_ij = exp(alpha q_i.k_j - LSE_i), dP = (dO V^T) o M/(1-p), dS = P o (dP - delta) recomputed per tile.
 // Same workgroup shape as the forward.
 // ===================================================================================================
-// LW: four more waves that fetch the tiles, as in the forward.
+// LW: four more waves that fetch the tiles, as in the forward.  Its Q / dO operands are pinned in vector registers, not
+// accumulation registers: a kernel that uses none of the latter gets all 256 registers of a wave as vector registers
+// (253 used at d = 160, no spills), otherwise the file is split 128 + 128 and the arithmetic is squeezed into half.
 template <int D, bool DROP, bool LW = false>
 __global__ __launch_bounds__(LW ? 512 : 256) void attn_bwd_dq_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                               const uint16_t* __restrict__ v, const uint16_t* __restrict__ o,
@@ -339,7 +341,10 @@ __global__ __launch_bounds__(LW ? 512 : 256) void attn_bwd_dq_mfma_kernel(AttnPa
   // These must have arrived before the tile loop: a wait left inside the loop would also wait for the direct
   // loads in flight there, which the compiler does not know about.
 #pragma unroll
-  for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+a"(qf[kc]), "+a"(dof[kc]));
+  for (int kc = 0; kc < KC; ++kc) {
+    if constexpr (LW) asm volatile("" : "+v"(qf[kc]), "+v"(dof[kc]));  // two waves per SIMD: no accumulation registers, so that all 256 are vector registers
+    else asm volatile("" : "+a"(qf[kc]), "+a"(dof[kc]));
+  }
   const float dl = dpart + __shfl_xor(dpart, 32, 64);
   if (ks == 0 && hh == 0 && i < P.s) delta[(size_t)bn * P.s + i] = dl;
   const float lse2 = lse[(size_t)bn * P.s + i_ld] * kLog2e;
@@ -536,10 +541,10 @@ static hipError_t bwd_dq_d(const AttnParams& P, const void* q, const void* k, co
                            float* delta, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
   {
-    // loader waves pay at d = 128 only (175B shard -11 %): at d = 160 they need 232 registers instead of 288 and gain
-    // nothing, at d = 64 / 96 several workgroups share a CU anyway (+5 %, +15 %).  SAR_DQLW = 0 / 1 forces the choice.
+    // loader waves: -12 % at d = 128 (175B shard), -3 % at d = 160 (530B shard; -6 % at s = 4096), nothing at d = 64, +16 %
+    // at d = 96, where several workgroups share a CU anyway.  SAR_DQLW = 0 / 1 forces the choice.
     const char* lw = getenv("SAR_DQLW");
-    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D == 128;
+    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D >= 128;
     if (use_lw) {
       if (P.thresh != 0)
         hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true, true>), dim3((unsigned)(nb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
