@@ -22,6 +22,7 @@ _SOURCES = {
     "attn_simple.hip": [],
     "attn_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
     "attn_mfma_cols.hip": [],
+    "attn_mfma_cols_small.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "attn_mfma_stored.hip": [],
     "rows.hip": [],
 }
