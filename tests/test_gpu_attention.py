@@ -133,6 +133,34 @@ def test_bf16_matrix_core_path_short_sequences(d, s, causal):
     _check_bf16_heads("short", sh, q, k, v, do, got, range(4))
 
 
+def test_random_shapes_and_kernel_variants(monkeypatch):
+    """A seeded sweep: head dimension, sequence length (any multiple of 8 up to 560), batch, heads, TP rank, p, mask and the
+    kernel variants (128-row forward, loader waves in the forward and in the dQ pass: forced on, forced off or left to
+    the library) drawn at random; every (batch, head) of every case against the oracle."""
+    import random
+    from gpu_util import run_attn
+    rng = random.Random(20240611)
+    for case in range(16):
+        d = rng.choice([64, 96, 128, 160])
+        s = 8 * rng.randint(1, 70)
+        b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
+        rank = rng.randrange(t)
+        p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
+        env = {}
+        for name in ("SAR_FWD128", "SAR_FWDLW", "SAR_DQLW"):
+            c = rng.choice([None, "0", "1"])
+            if c is None or (name == "SAR_FWD128" and s < 128):
+                monkeypatch.delenv(name, raising=False)
+            else:
+                monkeypatch.setenv(name, c)
+                env[name] = c
+        sh = oracle.AttnShape(s=s, b=b, a=A * t, h=A * t * d, t=t, rank=rank, p=p, seed=1000 + case, offset=7 * case, causal=causal)
+        q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=500 + case)
+        print(f"case {case}: d={d} s={s} b={b} A={A} t={t} rank={rank} p={p} causal={causal} {env}", flush=True)
+        got = run_attn(sh, "bf16", q, k, v, do)
+        _check_bf16_heads(f"sweep{case}", sh, q, k, v, do, got, range(b * A))
+
+
 def test_bf16_generic_path_other_head_dim():
     from gpu_util import run_attn
     sh = oracle.AttnShape(s=72, b=1, a=2, h=2 * 40, p=0.1, seed=3)
