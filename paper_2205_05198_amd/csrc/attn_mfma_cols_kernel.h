@@ -139,10 +139,28 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
           asm volatile("" : "+" SAR_COLS_ACC(dvacc[dt]));
         }
       }
+      // The operand reads run kAhead pairs of matrix instructions ahead, written out: the loads below are opaque
+      // memory operations to the compiler, which therefore never moves an LDS read up across one of them, and a
+      // read issued right before its matrix instruction leaves the whole LDS latency exposed, KC times.
+      constexpr int kAhead = 2;
+      bf16x8_t ka[kAhead], qa[kAhead], va[kAhead], da[kAhead];
+      const uint16_t* qrow = Qs + (32 * is + li) * KP + 8 * hh;
+      const uint16_t* drow = dOs + (32 * is + li) * KP + 8 * hh;
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) {
+        ka[a] = ld_frag(kw + 16 * a), qa[a] = ld_frag(qrow + 16 * a);
+        va[a] = ld_frag(vw + 16 * a), da[a] = ld_frag(drow + 16 * a);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
-        st = mfma32(ld_frag(kw + 16 * kc), ld_frag(Qs + (32 * is + li) * KP + 16 * kc + 8 * hh), st);
-        dd = mfma32(ld_frag(vw + 16 * kc), ld_frag(dOs + (32 * is + li) * KP + 16 * kc + 8 * hh), dd);
+        st = mfma32(ka[kc % kAhead], qa[kc % kAhead], st);
+        dd = mfma32(va[kc % kAhead], da[kc % kAhead], dd);
+        if (kc + kAhead < KC) {
+          ka[kc % kAhead] = ld_frag(kw + 16 * (kc + kAhead)), qa[kc % kAhead] = ld_frag(qrow + 16 * (kc + kAhead));
+          va[kc % kAhead] = ld_frag(vw + 16 * (kc + kAhead)), da[kc % kAhead] = ld_frag(drow + 16 * (kc + kAhead));
+        }
+        __builtin_amdgcn_sched_barrier(0);
         if constexpr (EVEN) {  // rounds 1 .. PER-1 of the Q tile, then of the dO tile
           constexpr int PER = DmaMap<D>::PER;
           static_assert(2 * (PER - 1) <= KC, "more load rounds than pairs of matrix instructions");
