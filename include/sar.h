@@ -79,8 +79,18 @@ typedef struct {
 sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
                          void* o, float* lse, void* stream);
 
-/* Bytes of scratch attn_core_bwd_recompute needs for this descriptor (0 on error). */
+/*
+ * Scratch of attn_core_bwd_recompute (0 on error).  The backward exists in two forms, chosen by the workspace it is given:
+ *   - workspace_bytes >= attn_core_bwd_workspace(desc): the region is recomputed ONCE.  The pass that forms dK, dV also
+ *     writes the bf16 dS tiles (2 bytes per score pair that the mask allows, in 64 x 64 tiles: 2 A b s^2 bytes, about half
+ *     of it under the causal mask) and dQ = alpha dS K is formed from them.  This scratch lives only inside the call;
+ *     nothing of size s x s is kept from the forward (Section 5).  bf16 with head dimension 64 / 96 / 128 / 160 only.
+ *   - workspace_bytes >= attn_core_bwd_workspace_min(desc) (one float per query row): the region is recomputed TWICE, once
+ *     per query block for dQ and once per key block for dK, dV; scratch is O(s).
+ * attn_core_bwd_workspace returns the first size while it stays below 4 GiB (s = 8192 with 16 heads: 1.1 GB), else the second.
+ */
 size_t attn_core_bwd_workspace(const sar_attn_desc* desc);
+size_t attn_core_bwd_workspace_min(const sar_attn_desc* desc);
 
 /*
  * attn_core_bwd_recompute -- backward of the region of Section 5: softmax P and the dropout mask are
@@ -89,8 +99,9 @@ size_t attn_core_bwd_workspace(const sar_attn_desc* desc);
  *   q, k, v, o, lse : in, exactly what attn_core_fwd received / produced
  *   d_o             : in, gradient of o, same layout and dtype
  *   dq, dk, dv      : out, same layout and dtype (may not alias inputs or each other)
- *   workspace       : device scratch of at least attn_core_bwd_workspace(desc) bytes, 16-byte
- *                     aligned; contents on entry are irrelevant, contents on exit unspecified
+ *   workspace       : device scratch of at least attn_core_bwd_workspace_min(desc) bytes, 16-byte
+ *                     aligned; contents on entry are irrelevant, contents on exit unspecified.  Its size
+ *                     selects the form of the backward (see attn_core_bwd_workspace).
  * Results are deterministic (no atomics).
  */
 sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
@@ -99,7 +110,19 @@ sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, con
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The two passes of attn_core_bwd_recompute as separate calls (same kernels, same arguments): the row
+ * The three launches of the recompute-once backward as separate calls (for timing each of them): `stages` is a subset of
+ *   1  delta_i = sum_k dO_ik O_ik into the workspace          (needs o, d_o)
+ *   2  dk, dv and the dS tiles into the workspace             (needs q, k, v, lse, d_o; reads delta)
+ *   4  dq from the dS tiles                                   (needs k; reads the tiles)
+ * run in this order on one stream with the same workspace (at least attn_core_bwd_workspace bytes of the once-form; see
+ * above) they equal attn_core_bwd_recompute.  Pointers that the chosen stages do not need may be NULL.
+ */
+sar_status attn_core_bwd_recompute_stages(const sar_attn_desc* desc, int stages, const void* q, const void* k, const void* v,
+                                          const void* o, const float* lse, const void* d_o, void* dq, void* dk, void* dv,
+                                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two passes of the recompute-twice backward as separate calls (same kernels, same arguments): the row
  * pass recomputes the region per query block and writes dq and the per-row term sum_k dO_ik O_ik into the
  * workspace; the column pass recomputes it per key block, reads that term back and writes dk, dv.
  * Row pass then column pass on one stream, with the same workspace, equals attn_core_bwd_recompute.
@@ -221,6 +244,16 @@ sar_status bias_gelu_fwd(const sar_rows_desc* desc, const void* x, const void* b
 size_t bias_gelu_bwd_workspace(const sar_rows_desc* desc);
 sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* x, const void* bias, void* dx, float* dbias,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Test and measurement hook, not part of the method: forces kernel variants that the library otherwise picks by shape
+ * (every variant computes the same result).  Each argument: -1 = the library's choice, 0 = off, 1 = on.
+ *   fwd_128_rows      forward with 128 instead of 64 query rows per workgroup (needs s >= 128)
+ *   fwd_loader_waves  forward with four extra waves that only fetch K / V tiles
+ *   dq_loader_waves   the same for the row pass of the recompute-twice backward
+ * Process-wide; not meant to be changed while another thread launches.
+ */
+void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves);
 
 /* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
 const char* sar_last_error(void);

@@ -24,6 +24,7 @@ _SOURCES = {
     "attn_mfma_cols.hip": [],
     "attn_mfma_cols_small.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "attn_mfma_stored.hip": [],
+    "attn_mfma_dsgemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "rows.hip": [],
 }
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -114,6 +115,9 @@ def load_library():
     protos = {
         "attn_core_fwd": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp]),
         "attn_core_bwd_workspace": (sz, [ad]),
+        "attn_core_bwd_workspace_min": (sz, [ad]),
+        "attn_core_bwd_recompute_stages": (ctypes.c_int, [ad, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "sar_test_force_variants": (None, [ctypes.c_int, ctypes.c_int, ctypes.c_int]),
         "attn_core_bwd_recompute": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dq": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dkdv": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
@@ -141,7 +145,8 @@ def load_library():
     return lib
 
 
-EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_recompute", "attn_core_bwd_recompute_dq",
+EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_workspace_min", "attn_core_bwd_recompute",
+           "attn_core_bwd_recompute_stages", "sar_test_force_variants", "attn_core_bwd_recompute_dq",
            "attn_core_bwd_recompute_dkdv", "attn_core_fwd_stored",
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
            "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
@@ -173,6 +178,20 @@ def attn_core_fwd(desc: AttnDesc, q, k, v, o, lse):
 
 def attn_core_bwd_workspace(desc: AttnDesc) -> int:
     return int(load_library().attn_core_bwd_workspace(ctypes.byref(desc)))
+
+
+def attn_core_bwd_workspace_min(desc: AttnDesc) -> int:
+    return int(load_library().attn_core_bwd_workspace_min(ctypes.byref(desc)))
+
+
+def sar_test_force_variants(fwd_128_rows: int = -1, fwd_loader_waves: int = -1, dq_loader_waves: int = -1):
+    load_library().sar_test_force_variants(fwd_128_rows, fwd_loader_waves, dq_loader_waves)
+
+
+def attn_core_bwd_recompute_stages(desc: AttnDesc, stages: int, q, k, v, o, lse, d_o, dq, dk, dv, workspace):
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().attn_core_bwd_recompute_stages(ctypes.byref(desc), stages, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                          _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), nbytes, _stream()))
 
 
 def attn_core_bwd_recompute(desc: AttnDesc, q, k, v, o, lse, d_o, dq, dk, dv, workspace):

@@ -6,15 +6,15 @@
 namespace sar {
 
 hipError_t launch_attn_bwd_dkdv_mfma_small(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
-                                           const float* delta, void* dk, void* dv, hipStream_t st);  // attn_mfma_cols_small.hip
+                                           const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);  // attn_mfma_cols_small.hip
 
 hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
-                                     const float* delta, void* dk, void* dv, hipStream_t st) {
+                                     const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
   switch (P.d) {
     case 64:
-    case 96: return launch_attn_bwd_dkdv_mfma_small(P, q, k, v, lse, dO, delta, dk, dv, st);
-    case 128: return bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, st);
-    case 160: return bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, st);
+    case 96: return launch_attn_bwd_dkdv_mfma_small(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    case 128: return bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    case 160: return bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -12,6 +12,14 @@
 
 namespace sar {
 
+// Two 16-byte stores per lane at (uniform base) + 16 lane and + 1 KB more: the wave's two dS operands of a step.  Written
+// with a scalar base so that the only vector register the addresses cost is a short-lived one (the kernel is within a
+// few registers of its limit, and a spilled or recomputed tile address sits on the critical path of every load).
+__device__ __forceinline__ void ds_store2(uint16_t* base, int lane, bf16x8_t a, bf16x8_t b) {
+  const uint32_t off = 16u * (uint32_t)lane;
+  asm volatile("global_store_dwordx4 %0, %1, %3\n\tglobal_store_dwordx4 %0, %2, %3 offset:1024" : : "v"(off), "v"(a), "v"(b), "s"(base) : "memory");
+}
+
 // ===================================================================================================
 // Backward, column-stationary pass.  Workgroup = 64 keys: wave = (kgp, is), kgp = 32-key group whose dK, dV
 // accumulators it keeps in registers, is = which 32 query rows of each 64-row tile it sweeps.
@@ -26,11 +34,14 @@ namespace sar {
 // per pair of score-tile matrix instructions instead of all at the top of the step: the L1 accepts one wave-wide
 // load per 16 cycles per CU, a pair of 32x32x16 instructions keeps a SIMD busy for 64, so four waves that each issue
 // one load per pair never queue behind each other (issued back to back, all four sit through all 44 loads).
-template <int D, bool DROP, bool EVEN>
+// WDS: the bf16 dS tiles are also written to ds_ws (layout: ds_tile_index / kDsTileElems of sar_internal.h; inside a tile
+// wave (kgp, is) owns two runs of 1 KB, one per 16-key group c, 16 bytes per lane), for the pass that forms dQ = alpha dS K
+// from them without recomputing anything.
+template <int D, bool DROP, bool EVEN, bool WDS = false>
 __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                                 const uint16_t* __restrict__ v, const float* __restrict__ lse,
                                                                 const uint16_t* __restrict__ dO, const float* __restrict__ delta,
-                                                                uint16_t* __restrict__ dk, uint16_t* __restrict__ dv) {
+                                                                uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, uint16_t* __restrict__ ds_ws) {
   constexpr int BN = 64, BI = 64, KP = D + 8, KC = D / 16, DT = D / 32;
   constexpr int TILE = 64 * KP;
   __shared__ __attribute__((aligned(16))) uint16_t smem[6 * TILE];
@@ -97,9 +108,22 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
 
   const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
   const float sc2 = P.scale * kLog2e;
+  if constexpr (WDS) dma_wait();  // the first loads; inside the loop only "all but the last two operations" is waited for
+  // WDS: this lane's 16 bytes of key group 0 in tile (it, kb) (key group 1: + 512 elements); the tile index grows by it + 1
+  // per step under the causal mask, by the number of key blocks without it
+  uint16_t* ds_tile = nullptr;                               // uniform: the wave's 2 KB of the tile
+  int64_t ds_step = 0;
+  if constexpr (WDS) {
+    ds_tile = ds_ws + ((int64_t)bn * ds_tiles_per_head(P) + ds_tile_index(P, it0, kb)) * kDsTileElems + (2 * is + kgp) * 1024;
+    ds_step = (P.causal ? (int64_t)(it0 + 1) : (int64_t)nit) * kDsTileElems;
+  }
   for (int it = it0; it < nit; ++it) {
     const int i0 = it * BI;
-    dma_wait();       // this wave's share of tile `it` (and, the first time, of K and V) has landed
+    // This wave's share of tile `it` (and, the first time, of K and V) has landed.  WDS: every step ends with exactly two
+    // dS stores per wave, issued after the step's loads; they need not have completed (waiting for them would cost the
+    // write latency in every step).
+    if constexpr (WDS) dma_wait_keep<2>();
+    else dma_wait();
     __syncthreads();  // ... and everybody's; nobody reads the other stage any more
     // EVEN: the first round of the next block's loads; the last step fetches its own block again (into the stage
     // that nobody reads any more) so that the step has one path
@@ -178,11 +202,14 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
       const int i = i0w + li;
       const float lse2 = lse_c[32 * is + li] * kLog2e, dl = delta_c[32 * is + li];
       const uint64_t rowG = headG + (uint64_t)min(i, P.s - 1) * (uint64_t)(P.s >> 3);
-      if (diag || i0w + 31 >= P.s) {  // uniform per wave: keys j > i and rows past the end get probability exp2(-inf) = 0
+      // uniform per wave: keys j > i, rows past the end and (WDS: their dS must be zero) keys past the end get
+      // probability exp2(-inf) = 0
+      if (diag || i0w + 31 >= P.s || (WDS && jw0 + 31 >= P.s)) {
         asm volatile("" ::: "memory");  // keep this a branch: most tiles skip it
+        const int jlim = i >= P.s ? -1 : (P.causal ? i : P.s - 1);  // last key that row i attends to
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (i >= P.s || (P.causal && jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i)) st[e] = -INFINITY;
+          if (jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > jlim) st[e] = -INFINITY;
       }
       bf16x8_t df[2], dsf[2];
 #pragma unroll
@@ -200,6 +227,7 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
         df[c] = pack8(dvv);
         dsf[c] = pack8(ds);
       }
+      if constexpr (WDS) ds_store2(ds_tile, lane, dsf[0], dsf[1]);
       // one-key-per-lane copies: T[i][key] = sum_k tile[i][k] I[k][key]
       float16_t tD, tS;
 #pragma unroll
@@ -221,6 +249,13 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
           dkacc[dt] = mfma32(ld_frag_tr_perm(Qs, KP, 32 * is + 16 * X, 32 * dt, lane), sT, dkacc[dt]);
         }
       }
+    } else if constexpr (WDS) {  // a quarter above the diagonal: its dS is zero (and the step still ends with two stores)
+      const u32x4_t zero = {0u, 0u, 0u, 0u};
+      ds_store2(ds_tile, lane, __builtin_bit_cast(bf16x8_t, zero), __builtin_bit_cast(bf16x8_t, zero));
+    }
+    if constexpr (WDS) {
+      ds_tile += ds_step;
+      if (P.causal) ds_step += kDsTileElems;
     }
     // Keep the loop-carried accumulators in the accumulation registers (AGPRs) across the back-edge; without
     // this the compiler copies all of them to VGPRs and back on every trip.
@@ -252,17 +287,25 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
 
 template <int D>
 static hipError_t bwd_dkdv_d(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO, const float* delta,
-                             void* dk, void* dv, hipStream_t st) {
+                             void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
   auto go = [&](auto kern) {
     hipLaunchKernelGGL(kern, dim3((unsigned)(nb * N)), dim3(256), 0, st, P, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse,
-                       (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv);
+                       (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv, ds_ws);
   };
   // interleaved loads pay at d = 160 only (530B shard -3 %, 1T -6 %, s = 4096 -3 %; d = 128 unchanged; d = 96, where two
   // workgroups share a CU and fill each other's stalls anyway, +2 %)
   constexpr bool kInterleave = D >= 160;
   const bool even = kInterleave && P.s % 64 == 0;
-  if (P.thresh != 0) {
+  if (ds_ws) {
+    if (P.thresh != 0) {
+      if (even) go(attn_bwd_dkdv_mfma_kernel<D, true, kInterleave, true>);
+      else go(attn_bwd_dkdv_mfma_kernel<D, true, false, true>);
+    } else {
+      if (even) go(attn_bwd_dkdv_mfma_kernel<D, false, kInterleave, true>);
+      else go(attn_bwd_dkdv_mfma_kernel<D, false, false, true>);
+    }
+  } else if (P.thresh != 0) {
     if (even) go(attn_bwd_dkdv_mfma_kernel<D, true, kInterleave>);
     else go(attn_bwd_dkdv_mfma_kernel<D, true, false>);
   } else {

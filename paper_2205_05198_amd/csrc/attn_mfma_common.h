@@ -61,6 +61,10 @@ __device__ __forceinline__ void dma4(const void* gaddr, uint32_t lds_base) {
 }
 // every direct load this wave has issued has landed in LDS
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// all but the N most recent vector-memory operations of this wave have completed (the counter covers loads and stores
+// alike and they complete in issue order): waits for direct loads without waiting for N stores or loads issued after them
+template <int N>
+__device__ __forceinline__ void dma_wait_keep() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
 // NW = number of waves that share the loads of a tile (the whole workgroup)
 template <int D, int NW = 4>

@@ -23,7 +23,7 @@
 //                                               dS / D moved to the transposed layout by an identity MFMA)
 // No s x s tensor is ever written; the dropout mask is regenerated from (seed, offset) in all three.
 #include "attn_mfma_common.h"
-#include <cstdlib>
+#include <atomic>
 #include <type_traits>
 
 namespace sar {
@@ -476,17 +476,36 @@ __global__ __launch_bounds__(LW ? 512 : 256) void attn_bwd_dq_mfma_kernel(AttnPa
 
 bool attn_mfma_supported(int d) { return d == 64 || d == 96 || d == 128 || d == 160; }
 
-// 128-row workgroups pay when there are more of them than CUs (256), so that the heaviest one does not set the pace,
+// 128-row workgroups pay when there are more of them than CUs (256 on this chip), so that the heaviest one does not set the pace,
 // and at the largest head dimension only (measured at d = 160: -19 % at s = 4096, -20 % at s = 8192, -21 % without the
 // mask, -14 % for 20 heads, -20 % for 32 heads; +14 % at the 16-head s = 2048 shape with its 256 workgroups; at d = 128
 // +4 % and +10 % with 768 and 384 workgroups, at d = 96 +9 % with 512).
-// The environment variable SAR_FWD128 = 0 / 1 forces the choice (tests, measurements).
+// sar_test_force_variants (tests, measurements) overrides the choice.
+static std::atomic<int> g_force_fwd128{-1}, g_force_fwdlw{-1}, g_force_dqlw{-1};  // -1: the library chooses; 0 / 1: forced
+void attn_mfma_force_variants(int fwd128, int fwdlw, int dqlw) {
+  g_force_fwd128 = fwd128;
+  g_force_fwdlw = fwdlw;
+  g_force_dqlw = dqlw;
+}
+
+// compute units of the current device, asked once
+static int cu_count() {
+  static std::atomic<int> cached{0};
+  int n = cached.load();
+  if (n > 0) return n;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+  cached = n;
+  return n;
+}
+
 static bool fwd_use_128(const AttnParams& P) {
   if (P.s < 128) return false;
-  const char* e = getenv("SAR_FWD128");
-  if (e && (e[0] == '0' || e[0] == '1')) return e[0] == '1';
+  const int f = g_force_fwd128.load();
+  if (f == 0 || f == 1) return f == 1;
   const int64_t wgs = (int64_t)((P.s + 127) / 128) * P.b * P.A;
-  return P.d >= 160 && (P.causal ? wgs > 256 : wgs >= 256);
+  const int cus = cu_count();
+  return P.d >= 160 && (P.causal ? wgs > cus : wgs >= cus);
 }
 
 template <int D>
@@ -504,9 +523,9 @@ static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const
   const int N = P.b * P.A, nrb = (P.s + 63) / 64;
   {
     // loader waves: measured -10 % at d = 160 (530B shard), -9 % at d = 128 (175B), -8 % at d = 64, +15 % at d = 96 (22B
-    // shard: three 4-wave workgroups share a CU there and fill each other's stalls).  SAR_FWDLW = 0 / 1 forces the choice.
-    const char* lw = getenv("SAR_FWDLW");
-    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D != 96;
+    // shard: three 4-wave workgroups share a CU there and fill each other's stalls).
+    const int lw = g_force_fwdlw.load();
+    const bool use_lw = (lw == 0 || lw == 1) ? lw == 1 : D != 96;
     if (use_lw) {
       if (P.thresh != 0)
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 2, true>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q,
@@ -542,9 +561,9 @@ static hipError_t bwd_dq_d(const AttnParams& P, const void* q, const void* k, co
   const int N = P.b * P.A, nb = (P.s + 63) / 64;
   {
     // loader waves: -12 % at d = 128 (175B shard), -3 % at d = 160 (530B shard; -6 % at s = 4096), nothing at d = 64, +16 %
-    // at d = 96, where several workgroups share a CU anyway.  SAR_DQLW = 0 / 1 forces the choice.
-    const char* lw = getenv("SAR_DQLW");
-    const bool use_lw = (lw && (lw[0] == '0' || lw[0] == '1')) ? lw[0] == '1' : D >= 128;
+    // at d = 96, where several workgroups share a CU anyway.
+    const int lw = g_force_dqlw.load();
+    const bool use_lw = (lw == 0 || lw == 1) ? lw == 1 : D >= 128;
     if (use_lw) {
       if (P.thresh != 0)
         hipLaunchKernelGGL((attn_bwd_dq_mfma_kernel<D, true, true>), dim3((unsigned)(nb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
@@ -577,7 +596,7 @@ hipError_t launch_attn_bwd_mfma(const AttnParams& P, const void* q, const void* 
     }
     if (e != hipSuccess) return e;
   }
-  if (passes & 2) e = launch_attn_bwd_dkdv_mfma(P, q, k, v, lse, dO, delta, dk, dv, st);
+  if (passes & 2) e = launch_attn_bwd_dkdv_mfma(P, q, k, v, lse, dO, delta, dk, dv, nullptr, st);
   return e;
 }
 

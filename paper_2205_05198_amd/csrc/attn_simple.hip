@@ -1,7 +1,7 @@
 // Attention core in plain fp32 arithmetic, one wavefront per score row (forward, dQ) or per score column
 // (dK, dV).  Serves (i) the fp32 dtype, (ii) the stored-activation baseline of Section 4.1 (P, M, D written
 // in the forward and read back in the backward), for any head dimension d % 4 == 0 up to 256.
-// The bf16 recompute path of Section 5 at the benchmark head dimensions lives in attn_mfma.hip.
+// The bf16 recompute path of Section 5 at the benchmark head dimensions lives in attn_mfma_rows.hip (forward, dQ pass) and attn_mfma_cols_kernel.h (dK/dV pass).
 #include "sar_device.h"
 #include "sar_internal.h"
 

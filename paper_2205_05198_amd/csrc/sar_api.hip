@@ -59,6 +59,17 @@ sar_status check_attn_desc(const sar_attn_desc* c, sar::AttnParams* P) {
 
 bool use_mfma(const sar_attn_desc* c, const sar::AttnParams& P) { return c->dtype == SAR_BF16 && sar::attn_mfma_supported(P.d) && c->scale > 0.f; }
 
+// The matrix-core kernels address a 64-row tile with 32-bit byte offsets from the tile's first row.
+sar_status check_mfma_limits(const sar::AttnParams& P) {
+  if (63 * P.stride_s * 2 + 2 * (int64_t)P.d >= (1ll << 31)) return fail(SAR_ERR_UNSUPPORTED, "stride_s (%lld) too large for the bf16 kernels", (long long)P.stride_s);
+  return SAR_OK;
+}
+
+// workspace of the backward: delta (one float per row) and, for the path that recomputes the region once, the dS tiles
+size_t delta_bytes(const sar::AttnParams& P) { return ((size_t)P.b * P.A * P.s * sizeof(float) + 255) / 256 * 256; }
+size_t ds_bytes(const sar::AttnParams& P) { return (size_t)P.b * P.A * (size_t)sar::ds_tiles_per_head(P) * sar::kDsTileElems * 2; }
+constexpr size_t kDsWorkspaceCap = 4ull << 30;  // above this attn_core_bwd_workspace asks for the two-pass backward's scratch only
+
 sar_status check_simple_limits(const sar::AttnParams& P) {
   if (sar::attn_simple_lds_bytes(P.s) > 160 * 1024) return fail(SAR_ERR_UNSUPPORTED, "s (%d) too long for this dtype / head dimension", P.s);
   return SAR_OK;
@@ -99,6 +110,7 @@ sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return fail(SAR_ERR_ALIGN, "attn_core_fwd: pointer not 16-byte aligned");
   hipError_t e;
   if (use_mfma(desc, P)) {
+    if ((st = check_mfma_limits(P)) != SAR_OK) return st;
     e = sar::launch_attn_fwd_mfma(P, q, k, v, o, lse, (hipStream_t)stream);
   } else {
     if ((st = check_simple_limits(P)) != SAR_OK) return st;
@@ -107,25 +119,48 @@ sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k
   return e == hipSuccess ? SAR_OK : hip_fail(e, "attn_core_fwd launch");
 }
 
+size_t attn_core_bwd_workspace_min(const sar_attn_desc* desc) {
+  sar::AttnParams P;
+  if (check_attn_desc(desc, &P) != SAR_OK) return 0;
+  return delta_bytes(P);  // delta_i = dO_i . O_i per row
+}
+
 size_t attn_core_bwd_workspace(const sar_attn_desc* desc) {
   sar::AttnParams P;
   if (check_attn_desc(desc, &P) != SAR_OK) return 0;
-  return ((size_t)P.b * P.A * P.s * sizeof(float) + 255) / 256 * 256;  // delta_i = dO_i . O_i per row
+  if (use_mfma(desc, P) && ds_bytes(P) <= kDsWorkspaceCap) return delta_bytes(P) + ds_bytes(P);
+  return delta_bytes(P);
 }
 
+void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves) {
+  sar::attn_mfma_force_variants(fwd_128_rows, fwd_loader_waves, dq_loader_waves);
+}
+
+// passes: two-pass backward, bit 0 = row pass, bit 1 = column pass.  stages (passes == 0): the backward that recomputes the
+// region once, bit 0 = delta, bit 1 = column pass + dS tiles, bit 2 = dQ from the tiles.  passes == 3 and stages == 7: the
+// whole backward, by whichever of the two the workspace allows.
 static sar_status bwd_recompute_impl(const char* who, const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o,
                                      const float* lse, const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
-                                     int passes, void* stream) {
+                                     int passes, int stages, void* stream) {
   sar::AttnParams P;
   sar_status st = check_attn_desc(desc, &P);
   if (st != SAR_OK) return st;
-  const bool rowp = passes & 1, colp = passes & 2;
-  if (!q || !k || !v || !lse || !d_o || (rowp && (!o || !dq)) || (colp && (!dk || !dv))) return fail(SAR_ERR_NULL, "%s: NULL tensor pointer", who);
+  const bool mfma = use_mfma(desc, P);
+  if (passes && stages) {  // the whole backward
+    if (mfma && workspace && workspace_bytes >= delta_bytes(P) + ds_bytes(P)) passes = 0;
+    else stages = 0;
+  }
+  if (stages && !mfma) return fail(SAR_ERR_UNSUPPORTED, "%s: the single-recompute backward needs bf16 and a head dimension of 64, 96, 128 or 160", who);
+  const bool rowp = (passes & 1) || (stages & 5), colp = (passes & 2) || (stages & 2);
+  const bool need_o = (passes & 1) || (stages & 1), need_dq = (passes & 1) || (stages & 4);
+  if (!k || !v || !lse || !d_o || ((passes || (stages & 2)) && !q) || (need_o && !o) || (need_dq && !dq) || (colp && (!dk || !dv)))
+    return fail(SAR_ERR_NULL, "%s: NULL tensor pointer", who);
+  (void)rowp;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) ||
       !aligned16(dv))
     return fail(SAR_ERR_ALIGN, "%s: pointer not 16-byte aligned", who);
   const void* ins[5] = {q, k, v, o, d_o};
-  void* outs[3] = {rowp ? dq : nullptr, colp ? dk : nullptr, colp ? dv : nullptr};
+  void* outs[3] = {need_dq ? dq : nullptr, colp ? dk : nullptr, colp ? dv : nullptr};
   for (int x = 0; x < 3; ++x) {
     if (!outs[x]) continue;
     for (int y = 0; y < 5; ++y)
@@ -133,12 +168,17 @@ static sar_status bwd_recompute_impl(const char* who, const sar_attn_desc* desc,
     for (int y = x + 1; y < 3; ++y)
       if (outs[x] == outs[y]) return fail(SAR_ERR_SHAPE, "%s: outputs may not alias each other", who);
   }
-  const size_t need = attn_core_bwd_workspace(desc);
+  const size_t need = stages ? delta_bytes(P) + ds_bytes(P) : delta_bytes(P);
   if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
   if (!aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
   hipError_t e;
-  if (use_mfma(desc, P)) {
-    e = sar::launch_attn_bwd_mfma(P, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace, passes, (hipStream_t)stream);
+  if (mfma) {
+    if ((st = check_mfma_limits(P)) != SAR_OK) return st;
+    if (stages)
+      e = sar::launch_attn_bwd_once_mfma(P, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace,
+                                         reinterpret_cast<uint16_t*>(static_cast<char*>(workspace) + delta_bytes(P)), stages, (hipStream_t)stream);
+    else
+      e = sar::launch_attn_bwd_mfma(P, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace, passes, (hipStream_t)stream);
   } else {
     if ((st = check_simple_limits(P)) != SAR_OK) return st;
     e = sar::launch_attn_bwd_simple(P, desc->dtype == SAR_BF16, q, k, v, o, lse, d_o, dq, dk, dv, (float*)workspace, nullptr, nullptr, nullptr, passes,
@@ -149,17 +189,24 @@ static sar_status bwd_recompute_impl(const char* who, const sar_attn_desc* desc,
 
 sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                    const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
-  return bwd_recompute_impl("attn_core_bwd_recompute", desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes, 3, stream);
+  return bwd_recompute_impl("attn_core_bwd_recompute", desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes, 3, 7, stream);
+}
+
+sar_status attn_core_bwd_recompute_stages(const sar_attn_desc* desc, int stages, const void* q, const void* k, const void* v, const void* o,
+                                          const float* lse, const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                                          void* stream) {
+  if (stages < 1 || stages > 7) return fail(SAR_ERR_SHAPE, "attn_core_bwd_recompute_stages: stages must be a non-empty subset of 1 | 2 | 4");
+  return bwd_recompute_impl("attn_core_bwd_recompute_stages", desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes, 0, stages, stream);
 }
 
 sar_status attn_core_bwd_recompute_dq(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                       const void* d_o, void* dq, void* workspace, size_t workspace_bytes, void* stream) {
-  return bwd_recompute_impl("attn_core_bwd_recompute_dq", desc, q, k, v, o, lse, d_o, dq, nullptr, nullptr, workspace, workspace_bytes, 1, stream);
+  return bwd_recompute_impl("attn_core_bwd_recompute_dq", desc, q, k, v, o, lse, d_o, dq, nullptr, nullptr, workspace, workspace_bytes, 1, 0, stream);
 }
 
 sar_status attn_core_bwd_recompute_dkdv(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const float* lse, const void* d_o,
                                         void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
-  return bwd_recompute_impl("attn_core_bwd_recompute_dkdv", desc, q, k, v, nullptr, lse, d_o, nullptr, dk, dv, workspace, workspace_bytes, 2, stream);
+  return bwd_recompute_impl("attn_core_bwd_recompute_dkdv", desc, q, k, v, nullptr, lse, d_o, nullptr, dk, dv, workspace, workspace_bytes, 2, 0, stream);
 }
 
 sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const void* k, const void* v, void* o, float* lse, void* Pst, uint8_t* Mst,
@@ -172,6 +219,7 @@ sar_status attn_core_fwd_stored(const sar_attn_desc* desc, const void* q, const 
     return fail(SAR_ERR_ALIGN, "attn_core_fwd_stored: pointer not 16-byte aligned");
   hipError_t e;
   if (use_mfma(desc, P) && sar::attn_mfma_stored_supported(P)) {
+    if ((st = check_mfma_limits(P)) != SAR_OK) return st;
     e = sar::launch_attn_fwd_mfma(P, q, k, v, o, lse, (hipStream_t)stream);
     if (e == hipSuccess) e = sar::launch_attn_store_pmd_mfma(P, q, k, lse, Pst, Mst, Dst, (hipStream_t)stream);
   } else {
@@ -191,11 +239,12 @@ sar_status attn_core_bwd_stored(const sar_attn_desc* desc, const void* q, const 
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(Pst) || !aligned16(Mst) || !aligned16(Dst) || !aligned16(d_o) ||
       !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return fail(SAR_ERR_ALIGN, "attn_core_bwd_stored: pointer not 16-byte aligned");
-  const size_t need = attn_core_bwd_workspace(desc);
+  const size_t need = delta_bytes(P);
   if (!workspace || workspace_bytes < need) return fail(SAR_ERR_WORKSPACE, "workspace needs %zu bytes, got %zu", need, workspace_bytes);
   if (!aligned16(workspace)) return fail(SAR_ERR_ALIGN, "workspace not 16-byte aligned");
   hipError_t e;
   if (use_mfma(desc, P) && sar::attn_mfma_stored_supported(P)) {
+    if ((st = check_mfma_limits(P)) != SAR_OK) return st;
     e = sar::launch_attn_bwd_stored_mfma(P, q, k, v, o, d_o, Pst, Mst, Dst, dq, dk, dv, (float*)workspace, (hipStream_t)stream);
   } else {
     if ((st = check_simple_limits(P)) != SAR_OK) return st;

@@ -19,6 +19,17 @@ struct AttnParams {
   uint64_t offset;              // Philox counter base
 };
 
+// dS tiles of the backward that recomputes the region once: one 64 x 64 bf16 tile per (batch*head, 64-row query tile `it`,
+// 64-key block `kb`), kDsTileElems elements each; under the causal mask only the tiles with kb <= it exist.
+static constexpr int kDsTileElems = 64 * 64;
+__host__ __device__ inline int64_t ds_tiles_per_head(const AttnParams& P) {
+  const int64_t nt = (P.s + 63) / 64;
+  return P.causal ? nt * (nt + 1) / 2 : nt * nt;
+}
+__host__ __device__ inline int64_t ds_tile_index(const AttnParams& P, int it, int kb) {
+  return P.causal ? (int64_t)it * (it + 1) / 2 + kb : (int64_t)it * ((P.s + 63) / 64) + kb;
+}
+
 struct RowsParams {
   int64_t rows, h, row_offset;
   float eps, p, keep_scale;
@@ -49,8 +60,15 @@ hipError_t launch_attn_fwd_mfma(const AttnParams& P, const void* q, const void* 
 hipError_t launch_attn_bwd_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                 const void* dO, void* dq, void* dk, void* dv, float* delta, int passes, hipStream_t st);
 
+// ds_ws != nullptr: the dS tiles are written there as well
 hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
-                                     const float* delta, void* dk, void* dv, hipStream_t st);
+                                     const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);
+// attn_mfma_dsgemm.hip: the backward that recomputes the region once.  stages: bit 0 = delta_i = dO_i . O_i, bit 1 = column
+// pass (dK, dV, and the dS tiles into ds_ws), bit 2 = dQ = alpha dS K from the tiles.
+hipError_t launch_attn_bwd_once_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                     const void* dO, void* dq, void* dk, void* dv, float* delta, uint16_t* ds_ws, int stages, hipStream_t st);
+// test hook: force kernel variants (-1 = the library's choice, 0 / 1 = off / on)
+void attn_mfma_force_variants(int fwd128, int fwdlw, int dqlw);
 
 // rows.hip: LayerNorm forward/backward and bias-dropout-add on [rows, h]
 hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* gamma, const void* beta, void* y, float* mean,

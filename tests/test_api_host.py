@@ -24,7 +24,7 @@ def lib():
 def test_exports_match_header(lib):
     hdr = open(os.path.join(ROOT, "include", "sar.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    names = re.findall(r"\b(?:sar_status|size_t|uint64_t|const char\*)\s+(\w+)\s*\(", hdr)
+    names = re.findall(r"\b(?:sar_status|size_t|uint64_t|void|const char\*)\s+(\w+)\s*\(", hdr)
     assert sorted(names) == sorted(binding.EXPORTS)
     for n in names:
         assert hasattr(lib, n), n
@@ -83,8 +83,18 @@ def test_attention_argument_errors(lib):
     assert "16" in sar.sar_last_error()
     # backward: workspace too small / missing, aliasing
     d = sar.AttnDesc.packed(**good)
-    need = lib.attn_core_bwd_workspace(ctypes.byref(d))
+    need = lib.attn_core_bwd_workspace_min(ctypes.byref(d))
     assert need >= 4 * 128 * 2
+    # the once-form of the backward also holds the dS tiles: 3 causal 64 x 64 bf16 tiles per head here
+    assert lib.attn_core_bwd_workspace(ctypes.byref(d)) == need + 2 * 3 * 64 * 64 * 2
+    dn = sar.AttnDesc.packed(**good, causal=0)
+    assert lib.attn_core_bwd_workspace(ctypes.byref(dn)) == need + 2 * 4 * 64 * 64 * 2
+    df = sar.AttnDesc.packed(**good, dtype=binding.SAR_F32)   # plain kernels: two-pass form only
+    assert lib.attn_core_bwd_workspace(ctypes.byref(df)) == lib.attn_core_bwd_workspace_min(ctypes.byref(df))
+    # the stage calls need the full workspace of the once-form, and bf16 at a matrix-core head dimension
+    assert lib.attn_core_bwd_recompute_stages(ctypes.byref(d), 7, *p[:9], p[9], need, st) == -6
+    assert lib.attn_core_bwd_recompute_stages(ctypes.byref(d), 0, *p[:9], p[9], 1 << 30, st) == -2
+    assert lib.attn_core_bwd_recompute_stages(ctypes.byref(df), 7, *p[:9], p[9], 1 << 30, st) == -3
     assert lib.attn_core_bwd_recompute(ctypes.byref(d), *p[:9], p[9], need - 1, st) == -6
     assert lib.attn_core_bwd_recompute(ctypes.byref(d), *p[:9], None, need, st) == -6
     assert lib.attn_core_bwd_recompute(ctypes.byref(d), *p[:6], p[0], p[7], p[8], p[9], need, st) == -2
@@ -106,7 +116,7 @@ def test_stored_baseline_argument_errors(lib):
     assert lib.attn_core_fwd_stored(ctypes.byref(d), *args, st) == -4
     assert lib.attn_core_fwd_stored(ctypes.byref(sar.AttnDesc.packed(s=100, b=1, a=2, h=128)), *p[:8], st) == -3
     # backward: desc, q, k, v, o, P, M, D, dO, dq, dk, dv, workspace, bytes
-    need = lib.attn_core_bwd_workspace(ctypes.byref(d))
+    need = lib.attn_core_bwd_workspace_min(ctypes.byref(d))
     for missing in range(11):
         args = list(p[:11]); args[missing] = None
         assert lib.attn_core_bwd_stored(ctypes.byref(d), *args, p[11], need, st) == -1, missing
