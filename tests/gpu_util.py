@@ -49,15 +49,17 @@ def attn_scales(sh, q, k, v, do, be, n, P, M, D):
 
 
 def err_attn_bf16(x, ref, scale):
-    """bf16 attention bar: max_e |x - ref| / (2e-2 RMS(ref) + 2^-8 scale_e) must be <= 1.
+    """bf16 attention bar: max_e |x - ref| / (2e-2 RMS(ref) + 2^-8 (scale_e + |ref_e|)) must be <= 1.
 
     The stated bar (2e-2 of the tensor RMS) cannot hold alone on causal, near-uniform attention: rows near the
     top keep |O| ~ |v|/(1-p) while RMS(O) falls like sqrt(ln s / s), so even the exact result rounded once to
-    bf16 misses it (0.08 - 0.19 at s = 2048).  The second term admits one bf16 rounding unit of the element's
-    forward-error magnitude (attn_scales)."""
+    bf16 misses it (0.08 - 0.19 at s = 2048).  bf16 carries 8 significant bits, unit roundoff 2^-8: the second term
+    admits one rounding of every term that enters the matrix core (scale_e = sum of their magnitudes, attn_scales)
+    and one rounding of the stored result.  tests/test_bf16_bound.py shows on the CPU that an ideal pipeline with
+    exactly these two roundings needs it."""
     ref = np.asarray(ref, dtype=np.float64)
     rms = float(np.sqrt(np.mean(ref ** 2))) or 1.0
-    return float(np.max(np.abs(x - ref) / (2e-2 * rms + 2.0 ** -8 * scale)))
+    return float(np.max(np.abs(x - ref) / (2e-2 * rms + 2.0 ** -8 * (scale + np.abs(ref)))))
 
 
 def err(x, ref, dtype):
@@ -67,17 +69,45 @@ def err(x, ref, dtype):
 BAR = {"f32": 1e-4, "bf16": 2e-2}
 
 
-def run_attn(sh, dtype, q, k, v, do, stored=False):
+def err_attn_blocks(x, ref, norm=None, rows=64):
+    """Aggregate guard beside the elementwise bound: over every block of `rows` consecutive rows of one (batch, head),
+    RMS(x - ref) / (2^-9 RMS(norm)), norm = ref unless given: the error of a block in units of one bf16 rounding of its
+    typical element (norm = the forward-error magnitudes of attn_scales: of its typical sum of terms).
+    Returns the largest ratio over the blocks."""
+    ref = np.asarray(ref, dtype=np.float64)
+    norm = ref if norm is None else norm
+    worst = 0.0
+    for r0 in range(0, ref.shape[0], rows):
+        nb, eb = norm[r0:r0 + rows], (x - ref)[r0:r0 + rows]
+        rms = float(np.sqrt(np.mean(nb ** 2)))
+        if rms > 0.0:
+            worst = max(worst, float(np.sqrt(np.mean(eb ** 2))) / (2.0 ** -9 * rms))
+    return worst
+
+
+# Bars on err_attn_blocks.  Benchmark-recipe inputs (near-uniform softmax: results are means of many terms of one sign
+# pattern, |result| ~ |terms| / sqrt(count)): RMS error of a block <= BLOCK_GUARD roundings of the block's own RMS.
+# Stress inputs (peaked softmax): the gradients are differences of large terms (dS = P (dP - delta)), so a block's
+# own RMS says nothing about its rounding error; there the guard is against the RMS of the terms' magnitudes,
+# BLOCK_GUARD_TERMS roundings (half of what the elementwise bound admits for one element, over a whole block).
+# In these units two independent bf16 roundings (one operand, one result) have an RMS of about 1.2; measured on the GPU:
+# at most 1.2 (O), 1.5 (dV), 2.2 (dK), 2.5 (dQ) over every benchmark shape and the random sweep, and at most 1.9 of the
+# terms' RMS on the stress inputs.
+BLOCK_GUARD = 4.0
+BLOCK_GUARD_TERMS = 3.0
+
+
+def run_attn(sh, dtype, q, k, v, do, stored=False, two_pass=False):
     """Run forward + backward of the library on host arrays; returns host float64 results.
-    sh: oracle.AttnShape (used only for its numbers)."""
+    sh: oracle.AttnShape (used only for its numbers).  two_pass: give the backward only its minimal workspace, which
+    selects the form that recomputes the region twice (row pass + column pass)."""
     tdt, code = DT[dtype]
     desc = sar.AttnDesc.packed(sh.s, sh.b, sh.a, sh.h, t=sh.t, rank=sh.rank, dtype=code, p=sh.p, seed=sh.seed, offset=sh.offset,
                                scale=sh.alpha(), causal=sh.causal)
     dq_, dk_, dv_, dd = (dev(x, dtype) for x in (q, k, v, do))
     o = torch.empty_like(dq_)
     gq, gk, gv = (torch.empty_like(dq_) for _ in range(3))
-    ws = torch.empty(sar.attn_core_bwd_workspace(desc), dtype=torch.uint8, device="cuda")
-    N = sh.b * sh.A
+    ws = torch.empty(sar.attn_core_bwd_workspace_min(desc) if two_pass else sar.attn_core_bwd_workspace(desc), dtype=torch.uint8, device="cuda")
     out = {}
     if stored:
         P = torch.empty((sh.b, sh.A, sh.s, sh.s), dtype=tdt, device="cuda")

@@ -1,8 +1,12 @@
 """GPU parity: the HIP attention core against the fp64 oracle, through the C ABI.
 
-Bars (written here, as the acceptance criterion states them): fp32 path 1e-4 in
-max_e |x-ref| / max(|ref_e|, RMS(ref)); bf16 path 2e-2 in max_e |x-ref| / RMS(ref); dropout mask and byte
-counts bit-exact."""
+Bars: fp32 path 1e-4 in max_e |x-ref| / max(|ref_e|, RMS(ref)).  bf16 attention outputs and gradients, per (batch, head):
+elementwise |x - ref|_e <= 2e-2 RMS(ref) + 2^-8 (scale_e + |ref_e|), scale_e = the sum of the magnitudes of the terms that
+make up element e: one bf16 rounding (unit roundoff 2^-8) of every term and one of the result (the stated 2e-2 RMS alone
+cannot hold for any bf16 store on causal near-uniform rows, whose first rows are ~sqrt(s) times the tensor RMS), AND per
+block of 64 rows RMS(x - ref) <= 4 x 2^-9 RMS(ref of the block), which judges late rows by their own size (stress inputs
+with a peaked softmax, whose gradients are differences of large terms: <= 3 x 2^-9 RMS(scale of the block)).  Dropout masks and byte counts bit-exact (tests/test_gpu_attention_masks.py observes the
+masks of the fused kernels directly)."""
 import sys
 
 import numpy as np
@@ -28,21 +32,47 @@ def _oracle(sh, q, k, v, do, heads=None):
     return {**f, **g}
 
 
-def _check_bf16_heads(tag, sh, q, k, v, do, got, heads):
-    """bf16 attention bar per (batch, head): |x - ref| <= 2e-2 RMS(ref) + 2^-8 * forward-error magnitude."""
-    from gpu_util import attn_scales, err_attn_bf16
+@pytest.fixture(autouse=True)
+def _library_picks_variants():
+    """Every test starts and ends with the library choosing its kernel variants."""
+    import paper_2205_05198_amd as sar
+    sar.sar_test_force_variants(-1, -1, -1)
+    yield
+    sar.sar_test_force_variants(-1, -1, -1)
+
+
+def _check_bf16_heads(tag, sh, q, k, v, do, got, heads, peaked=False):
+    """bf16 attention bar per (batch, head): |x - ref| <= 2e-2 RMS(ref) + 2^-8 * forward-error magnitude, and the
+    64-row-block RMS guard (against the block's own RMS, or, for `peaked` stress inputs, against the RMS of the terms'
+    magnitudes).  The oracle runs on groups of consecutive heads at once (one thread per head)."""
+    from gpu_util import BLOCK_GUARD, BLOCK_GUARD_TERMS, attn_scales, err_attn_blocks, err_attn_bf16
+    heads = sorted(heads)
+    group = max(1, oracle.num_threads())
+    runs = []   # maximal runs of consecutive (batch, head) indices, at most `group` long
     for bn in heads:
-        be, n = bn // sh.A, bn % sh.A
-        f = oracle.attn_fwd(sh, q, k, v, materialise=True, heads=(bn, bn + 1))
-        g = oracle.attn_bwd(sh, q, k, v, do, heads=(bn, bn + 1))
-        sc = attn_scales(sh, q, k, v, do, be, n, f["P"][0], f["M"][0].astype(np.float64), f["D"][0])
+        if runs and runs[-1][1] == bn and bn - runs[-1][0] < group:
+            runs[-1][1] = bn + 1
+        else:
+            runs.append([bn, bn + 1])
+    for lo, hi in runs:
+        f = oracle.attn_fwd(sh, q, k, v, materialise=True, heads=(lo, hi))
+        g = oracle.attn_bwd(sh, q, k, v, do, heads=(lo, hi))
         ref = {**f, **g}
-        for nm in ("o", "dq", "dk", "dv"):
-            e = err_attn_bf16(got[nm][:, be, n], ref[nm][:, be, n], sc[nm])
-            print(f"  {tag}[{bn}] {nm}: {e:.3f} of the bound", flush=True)
-            assert e <= 1.0, (tag, bn, nm, e)
-        lref = ref["lse"][be, n]
-        assert np.max(np.abs(got["lse"][be, n] - lref)) < 2e-3 * (1.0 + np.max(np.abs(lref)))
+        for bn in range(lo, hi):
+            be, n = bn // sh.A, bn % sh.A
+            sc = attn_scales(sh, q, k, v, do, be, n, f["P"][bn - lo], f["M"][bn - lo].astype(np.float64), f["D"][bn - lo])
+            for nm in ("o", "dq", "dk", "dv"):
+                e = err_attn_bf16(got[nm][:, be, n], ref[nm][:, be, n], sc[nm])
+                eb = err_attn_blocks(got[nm][:, be, n], ref[nm][:, be, n])
+                et = err_attn_blocks(got[nm][:, be, n], ref[nm][:, be, n], sc[nm])
+                print(f"  {tag}[{bn}] {nm}: {e:.3f} of the bound, block RMS error {eb:.2f} x 2^-9 of the block, {et:.3f} x 2^-9 of its terms", flush=True)
+                assert e <= 1.0, (tag, bn, nm, e)
+                if peaked:
+                    assert et <= BLOCK_GUARD_TERMS, (tag, bn, nm, et)
+                else:
+                    assert eb <= BLOCK_GUARD, (tag, bn, nm, eb)
+            lref = ref["lse"][be, n]
+            assert np.max(np.abs(got["lse"][be, n] - lref)) < 2e-3 * (1.0 + np.max(np.abs(lref)))
 
 
 def test_tiny_fp32_workload():
@@ -78,26 +108,29 @@ def test_fp32_shapes(s, b, a, t, rank, d, p, std, outlier):
     assert np.max(np.abs(got["lse"] - ref["lse"]) / (1.0 + np.abs(ref["lse"]))) < 1e-5
 
 
+@pytest.mark.parametrize("two_pass", [False, True])
 @pytest.mark.parametrize("d", [64, 96, 128, 160])
 @pytest.mark.parametrize("s,b,A,p,std,causal", [(200, 2, 2, 0.1, None, 1), (328, 1, 3, 0.25, 1.0, 1), (200, 1, 2, 0.1, None, 0), (264, 1, 1, 0.0, 1.0, 0),
-                                                 (200, 1, 2, 0.0, None, 1)])
-def test_bf16_matrix_core_path_small(d, s, b, A, p, std, causal):
-    """Several 64-key tiles and 64-row blocks plus a ragged tail (s % 64 = 8), every benchmark head dimension;
-    causal = 0 is the encoder variant (every key), including p = 0."""
+                                                 (200, 1, 2, 0.0, None, 1), (256, 1, 2, 0.1, 4.0, 1)])
+def test_bf16_matrix_core_path_small(d, s, b, A, p, std, causal, two_pass):
+    """Several 64-key tiles and 64-row blocks plus a ragged tail (s % 64 = 8), every benchmark head dimension, both forms
+    of the backward (region recomputed once / twice); causal = 0 is the encoder variant (every key), including p = 0;
+    std = 4 is the stress input on the matrix cores (Q, K ~ 4 N(0,1): a peaked softmax, plus one planted outlier score)."""
     from gpu_util import run_attn
     sh = oracle.AttnShape(s=s, b=b, a=A * 2, h=A * 2 * d, t=2, rank=1, p=p, seed=1234, offset=(1 << 33) + 5, causal=causal)
     q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=9, qk_std=std, outlier=std is not None)
-    print(f"bf16 s={s} b={b} A={A} d={d} p={p} std={std}", flush=True)
-    got = run_attn(sh, "bf16", q, k, v, do)
-    _check_bf16_heads("bf16", sh, q, k, v, do, got, range(b * A))
+    print(f"bf16 s={s} b={b} A={A} d={d} p={p} std={std} two_pass={two_pass}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
+    _check_bf16_heads("bf16", sh, q, k, v, do, got, range(b * A), peaked=std is not None)
 
 
 @pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1)])
-def test_forward_with_128_row_workgroups(d, s, causal, monkeypatch):
+def test_forward_with_128_row_workgroups(d, s, causal):
     """The forward kernel with 128 query rows per workgroup (chosen by the library for long sequences) forced on small
     ragged shapes: lower and upper row groups end on different tiles under the mask, the last block is partly empty."""
+    import paper_2205_05198_amd as sar
     from gpu_util import run_attn
-    monkeypatch.setenv("SAR_FWD128", "1")
+    sar.sar_test_force_variants(1, -1, -1)
     sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=5, causal=causal)
     q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=17)
     print(f"fwd128 d={d} s={s} causal={causal}", flush=True)
@@ -105,39 +138,41 @@ def test_forward_with_128_row_workgroups(d, s, causal, monkeypatch):
     _check_bf16_heads("fwd128", sh, q, k, v, do, got, range(2))
 
 
-@pytest.mark.parametrize("lw", ["0", "1"])
+@pytest.mark.parametrize("lw", [0, 1])
 @pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (96, 200, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1)])
-def test_forward_with_and_without_loader_waves(d, s, causal, lw, monkeypatch):
+def test_forward_with_and_without_loader_waves(d, s, causal, lw):
     """The 64-row forward kernel and the dQ pass with (8 waves) and without (4 waves) their tile-fetching waves, both forced
     whatever the library would pick for the head dimension, on ragged shapes (the last tile is fetched with clamped rows)."""
+    import paper_2205_05198_amd as sar
     from gpu_util import run_attn
-    monkeypatch.setenv("SAR_FWDLW", lw)
-    monkeypatch.setenv("SAR_DQLW", lw)
-    monkeypatch.setenv("SAR_FWD128", "0")
+    sar.sar_test_force_variants(0, lw, lw)
     sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=5, causal=causal)
     q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=19)
     print(f"fwd loader waves={lw} d={d} s={s} causal={causal}", flush=True)
-    got = run_attn(sh, "bf16", q, k, v, do)
-    _check_bf16_heads("fwd-lw" + lw, sh, q, k, v, do, got, range(2))
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=True)   # the row pass with loader waves belongs to the two-pass backward
+    _check_bf16_heads(f"fwd-lw{lw}", sh, q, k, v, do, got, range(2))
 
 
+@pytest.mark.parametrize("two_pass", [False, True])
 @pytest.mark.parametrize("d,s,causal", [(160, 8, 1), (64, 24, 1), (128, 64, 1), (160, 72, 1), (96, 40, 0), (160, 56, 0)])
-def test_bf16_matrix_core_path_short_sequences(d, s, causal):
+def test_bf16_matrix_core_path_short_sequences(d, s, causal, two_pass):
     """Sequences of at most one or two tiles on the matrix-core kernels: the only tile is ragged (rows past the end are
     fetched clamped and masked), a workgroup has a single step, three of four waves may have nothing but masked keys."""
     from gpu_util import run_attn
     sh = oracle.AttnShape(s=s, b=2, a=2, h=2 * d, p=0.1, seed=9, causal=causal)
     q, k, v, do = attn_inputs(s, 2, 2, d, "bf16", seed=23)
-    print(f"short d={d} s={s} causal={causal}", flush=True)
-    got = run_attn(sh, "bf16", q, k, v, do)
+    print(f"short d={d} s={s} causal={causal} two_pass={two_pass}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
     _check_bf16_heads("short", sh, q, k, v, do, got, range(4))
 
 
-def test_random_shapes_and_kernel_variants(monkeypatch):
-    """A seeded sweep: head dimension, sequence length (any multiple of 8 up to 560), batch, heads, TP rank, p, mask and the
-    kernel variants (128-row forward, loader waves in the forward and in the dQ pass: forced on, forced off or left to
-    the library) drawn at random; every (batch, head) of every case against the oracle."""
+def test_random_shapes_and_kernel_variants():
+    """A seeded sweep: head dimension, sequence length (any multiple of 8 up to 560), batch, heads, TP rank, p, mask, the
+    form of the backward (region recomputed once or twice) and the kernel variants (128-row forward, loader waves in the
+    forward and in the row pass: forced on, forced off or left to the library) drawn at random; every (batch, head) of
+    every case against the oracle."""
     import random
+    import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     rng = random.Random(20240611)
     for case in range(16):
@@ -146,18 +181,15 @@ def test_random_shapes_and_kernel_variants(monkeypatch):
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = {}
-        for name in ("SAR_FWD128", "SAR_FWDLW", "SAR_DQLW"):
-            c = rng.choice([None, "0", "1"])
-            if c is None or (name == "SAR_FWD128" and s < 128):
-                monkeypatch.delenv(name, raising=False)
-            else:
-                monkeypatch.setenv(name, c)
-                env[name] = c
+        env = [rng.choice([-1, 0, 1]) for _ in range(3)]
+        if s < 128:
+            env[0] = -1
+        sar.sar_test_force_variants(*env)
+        two_pass = case % 2 == 1
         sh = oracle.AttnShape(s=s, b=b, a=A * t, h=A * t * d, t=t, rank=rank, p=p, seed=1000 + case, offset=7 * case, causal=causal)
         q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=500 + case)
-        print(f"case {case}: d={d} s={s} b={b} A={A} t={t} rank={rank} p={p} causal={causal} {env}", flush=True)
-        got = run_attn(sh, "bf16", q, k, v, do)
+        print(f"case {case}: d={d} s={s} b={b} A={A} t={t} rank={rank} p={p} causal={causal} variants={env} two_pass={two_pass}", flush=True)
+        got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
         _check_bf16_heads(f"sweep{case}", sh, q, k, v, do, got, range(b * A))
 
 
@@ -223,18 +255,42 @@ def test_recompute_equals_stored_and_is_deterministic():
     assert not np.array_equal(r1["o"], r3["o"])
 
 
-@pytest.mark.parametrize("name,heads", [("530B", (0, 15)), ("22B", (13,)), ("175B", (7,)), ("1T", (19,))])
-def test_full_size_sampled_heads(name, heads):
-    """Benchmark shapes in the launch configuration the benchmark times; the oracle checks whole (batch, head)
-    slices one by one."""
+@pytest.mark.parametrize("name,two_pass", [("530B", False), ("530B", True), ("22B", False), ("175B", False), ("1T", False)])
+def test_full_size_every_head(name, two_pass):
+    """Benchmark shapes in the launch configuration the benchmark times: every (batch, head) of the shard against the
+    oracle (16 at 530B, 32 at 22B, 12 at 175B, 20 at 1T); at 530B both forms of the backward."""
     from gpu_util import run_attn
     w = WORKLOADS[name]
     sh = oracle.AttnShape(s=w.s, b=w.b, a=w.a, h=w.h, t=w.t, rank=3, p=w.p, seed=w.seed)
     q, k, v, do = attn_inputs(w.s, w.b, w.A, w.d, "bf16", seed=w.seed)
-    print(f"{name}: s={w.s} b={w.b} A={w.A} d={w.d}", flush=True)
-    got = run_attn(sh, "bf16", q, k, v, do)
-    _check_bf16_heads(name, sh, q, k, v, do, got, heads)
+    print(f"{name}: s={w.s} b={w.b} A={w.A} d={w.d} two_pass={two_pass}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
+    _check_bf16_heads(name, sh, q, k, v, do, got, range(w.b * w.A))
     sys.stdout.flush()
+
+
+def test_stress_inputs_full_length():
+    """The stress input at the benchmark's sequence length on the matrix cores: Q, K ~ 4 N(0,1) (score std ~ 16 sqrt(d) alpha:
+    a sharply peaked softmax whose running maximum moves many times) plus a planted outlier, two heads of 160."""
+    from gpu_util import run_attn
+    s, d = 2048, 160
+    sh = oracle.AttnShape(s=s, b=1, a=2, h=2 * d, p=0.1, seed=4321, offset=17)
+    q, k, v, do = attn_inputs(s, 1, 2, d, "bf16", seed=71, qk_std=4.0, outlier=True)
+    print("bf16 stress s=2048 d=160", flush=True)
+    for two_pass in (False, True):
+        got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
+        _check_bf16_heads(f"stress-{'twice' if two_pass else 'once'}", sh, q, k, v, do, got, range(2), peaked=True)
+
+
+def test_sequence_8192_single_head():
+    """s = 8192 at the 530B head dimension (128 tiles per row block, 128-row forward workgroups): one head against the oracle."""
+    from gpu_util import run_attn
+    s, d = 8192, 160
+    sh = oracle.AttnShape(s=s, b=1, a=8, h=8 * d, t=8, rank=2, p=0.1, seed=1234, offset=5)
+    q, k, v, do = attn_inputs(s, 1, 1, d, "bf16", seed=67)
+    print("bf16 s=8192 one head", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    _check_bf16_heads("s8192", sh, q, k, v, do, got, range(1))
 
 
 def test_longer_sequence_single_head():
@@ -248,11 +304,12 @@ def test_longer_sequence_single_head():
     _check_bf16_heads("s4096", sh, q, k, v, do, got, range(1))
 
 
-def test_longer_sequence_single_head_128_row_workgroups(monkeypatch):
+def test_longer_sequence_single_head_128_row_workgroups():
     """The same with the forward's 128-row workgroups (what the library picks at this head dimension once there are more
     row blocks than CUs): 32 row blocks, up to 64 tiles each."""
+    import paper_2205_05198_amd as sar
     from gpu_util import run_attn
-    monkeypatch.setenv("SAR_FWD128", "1")
+    sar.sar_test_force_variants(1, -1, -1)
     s, d = 4096, 160
     sh = oracle.AttnShape(s=s, b=1, a=8, h=8 * d, t=8, rank=5, p=0.1, seed=1234, offset=99)
     q, k, v, do = attn_inputs(s, 1, 1, d, "bf16", seed=61)
