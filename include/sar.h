@@ -110,6 +110,21 @@ sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, con
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * attn_core_bwd_recompute_noalloc -- for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same backward as attn_core_bwd_recompute in
+ * its recompute-twice form (same kernels, same results bit for bit), with the scratch (one float per query row) in a
+ * buffer that is built into the library: attn_core_bwd_noalloc_max_bytes() bytes (1 MiB) per GPU, held until the process
+ * ends.  The call allocates and frees nothing.  b * (a/t) * s * 4 bytes (rounded up to 256) beyond that size return
+ * SAR_ERR_UNSUPPORTED (530B shard: 131 072 bytes).  Every call on a GPU uses that GPU's one buffer: calls that overlap in
+ * time on one GPU (different streams, or different threads) race; calls on one stream are ordered and safe.  The buffer's
+ * earlier contents do not matter (every byte read is written first by the same call).
+ */
+size_t attn_core_bwd_noalloc_max_bytes(void);
+sar_status attn_core_bwd_recompute_noalloc(const sar_attn_desc* desc, const void* q, const void* k, const void* v,
+                                           const void* o, const float* lse, const void* d_o,
+                                           void* dq, void* dk, void* dv, void* stream);
+
+/*
  * The three launches of the recompute-once backward as separate calls (for timing each of them): `stages` is a subset of
  *   1  delta_i = sum_k dO_ik O_ik into the workspace          (needs o, d_o)
  *   2  dk, dv and the dS tiles into the workspace             (needs q, k, v, lse, d_o; reads delta)

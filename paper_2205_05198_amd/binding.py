@@ -118,6 +118,8 @@ def load_library():
         "attn_core_bwd_workspace_min": (sz, [ad]),
         "attn_core_bwd_recompute_stages": (ctypes.c_int, [ad, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "sar_test_force_variants": (None, [ctypes.c_int, ctypes.c_int, ctypes.c_int]),
+        "attn_core_bwd_noalloc_max_bytes": (sz, []),
+        "attn_core_bwd_recompute_noalloc": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "attn_core_bwd_recompute": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dq": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "attn_core_bwd_recompute_dkdv": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
@@ -146,7 +148,8 @@ def load_library():
 
 
 EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_workspace_min", "attn_core_bwd_recompute",
-           "attn_core_bwd_recompute_stages", "sar_test_force_variants", "attn_core_bwd_recompute_dq",
+           "attn_core_bwd_recompute_stages", "sar_test_force_variants", "attn_core_bwd_noalloc_max_bytes",
+           "attn_core_bwd_recompute_noalloc", "attn_core_bwd_recompute_dq",
            "attn_core_bwd_recompute_dkdv", "attn_core_fwd_stored",
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
            "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
@@ -192,6 +195,15 @@ def attn_core_bwd_recompute_stages(desc: AttnDesc, stages: int, q, k, v, o, lse,
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().attn_core_bwd_recompute_stages(ctypes.byref(desc), stages, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
                                                           _ptr(dq), _ptr(dk), _ptr(dv), _ptr(workspace), nbytes, _stream()))
+
+
+def attn_core_bwd_noalloc_max_bytes() -> int:
+    return int(load_library().attn_core_bwd_noalloc_max_bytes())
+
+
+def attn_core_bwd_recompute_noalloc(desc: AttnDesc, q, k, v, o, lse, d_o, dq, dk, dv):
+    _check(load_library().attn_core_bwd_recompute_noalloc(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o),
+                                                           _ptr(dq), _ptr(dk), _ptr(dv), _stream()))
 
 
 def attn_core_bwd_recompute(desc: AttnDesc, q, k, v, o, lse, d_o, dq, dk, dv, workspace):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "sar_internal.h"
 
@@ -96,6 +97,34 @@ sar_status check_rows_desc(const sar_rows_desc* c, sar::RowsParams* P) {
   return SAR_OK;
 }
 
+// Scratch of attn_core_bwd_recompute_noalloc: one array per GPU, part of the loaded code object, held until the process
+// ends.  In host code the array's name is only a handle; its device address on the current GPU comes from
+// hipGetSymbolAddress, asked once per device, and is what the kernels get.
+constexpr size_t kStaticScratchBytes = 1u << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+sar_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(SAR_ERR_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return SAR_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -190,6 +219,23 @@ static sar_status bwd_recompute_impl(const char* who, const sar_attn_desc* desc,
 sar_status attn_core_bwd_recompute(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
                                    const void* d_o, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
   return bwd_recompute_impl("attn_core_bwd_recompute", desc, q, k, v, o, lse, d_o, dq, dk, dv, workspace, workspace_bytes, 3, 7, stream);
+}
+
+size_t attn_core_bwd_noalloc_max_bytes(void) { return kStaticScratchBytes; }
+
+sar_status attn_core_bwd_recompute_noalloc(const sar_attn_desc* desc, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                           const void* d_o, void* dq, void* dk, void* dv, void* stream) {
+  sar::AttnParams P;
+  sar_status st = check_attn_desc(desc, &P);
+  if (st != SAR_OK) return st;
+  const size_t need = delta_bytes(P);
+  if (need > kStaticScratchBytes)
+    return fail(SAR_ERR_UNSUPPORTED, "attn_core_bwd_recompute_noalloc: b * a/t * s = %lld rows need %zu bytes of scratch, the built-in buffer holds %zu",
+                (long long)P.b * P.A * P.s, need, kStaticScratchBytes);
+  void* ws = nullptr;
+  if ((st = static_scratch(&ws)) != SAR_OK) return st;
+  // the two-pass form: its only scratch is one float per query row, written by the row pass before the column pass reads it
+  return bwd_recompute_impl("attn_core_bwd_recompute_noalloc", desc, q, k, v, o, lse, d_o, dq, dk, dv, ws, need, 3, 0, stream);
 }
 
 sar_status attn_core_bwd_recompute_stages(const sar_attn_desc* desc, int stages, const void* q, const void* k, const void* v, const void* o,
