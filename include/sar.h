@@ -270,6 +270,18 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
  */
 void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves);
 
+/*
+ * Measurement hooks, not part of the method: the rates this GPU attains on the two rooflines that bound the kernels above.
+ *   sar_bench_mfma  enqueues a register-resident loop of `iters` x 4 independent 32x32x16 bf16 matrix instructions per wave,
+ *                   8 waves on every CU; *flops_out (host) receives the floating-point operations the launch performs;
+ *                   sink: device, at least 4 bytes, never written in practice.
+ *   sar_bench_copy  enqueues a plain copy of `bytes` (a multiple of 16, 16-byte aligned device pointers) from src to dst:
+ *                   `bytes` read and `bytes` written.
+ * The caller times them (events on `stream`).  They set no sar_last_error text.
+ */
+sar_status sar_bench_mfma(int iters, float* sink, double* flops_out, void* stream);
+sar_status sar_bench_copy(const void* src, void* dst, size_t bytes, void* stream);
+
 /* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
 const char* sar_last_error(void);
 

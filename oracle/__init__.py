@@ -22,7 +22,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "sar_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
-CFLAGS = ["-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
+CFLAGS = ["-O3", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra"]
 
 
 def build(force: bool = False) -> str:

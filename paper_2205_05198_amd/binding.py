@@ -26,6 +26,7 @@ _SOURCES = {
     "attn_mfma_stored.hip": [],
     "attn_mfma_dsgemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "rows.hip": [],
+    "microbench.hip": [],
 }
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wno-inline-asm", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -138,6 +139,8 @@ def load_library():
         "bias_gelu_fwd": (ctypes.c_int, [rd, vp, vp, vp, vp]),
         "bias_gelu_bwd_workspace": (sz, [rd]),
         "bias_gelu_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "sar_bench_mfma": (ctypes.c_int, [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]),
+        "sar_bench_copy": (ctypes.c_int, [vp, vp, sz, vp]),
         "sar_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in protos.items():
@@ -154,7 +157,7 @@ EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_workspace_
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
            "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
            "bias_dropout_add_bwd_workspace", "bias_dropout_add_bwd", "bias_gelu_fwd", "bias_gelu_bwd_workspace", "bias_gelu_bwd",
-           "sar_last_error"]
+           "sar_bench_mfma", "sar_bench_copy", "sar_last_error"]
 
 
 def _ptr(t):
@@ -173,6 +176,22 @@ def _check(status: int):
 
 def sar_last_error() -> str:
     return load_library().sar_last_error().decode()
+
+
+def sar_bench_mfma(iters: int, sink) -> float:
+    """Enqueue the matrix-core loop; returns the floating-point operations of the launch."""
+    fl = ctypes.c_double(0.0)
+    st = load_library().sar_bench_mfma(iters, _ptr(sink), ctypes.byref(fl), _stream())
+    if st != 0:
+        raise SarError(st, "sar_bench_mfma")
+    return fl.value
+
+
+def sar_bench_copy(src, dst):
+    n = src.numel() * src.element_size()
+    st = load_library().sar_bench_copy(_ptr(src), _ptr(dst), n, _stream())
+    if st != 0:
+        raise SarError(st, "sar_bench_copy")
 
 
 def attn_core_fwd(desc: AttnDesc, q, k, v, o, lse):

@@ -215,12 +215,14 @@ __global__ __launch_bounds__(256, D <= 96 ? 2 : 1) void attn_bwd_dkdv_mfma_kerne
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
         const int jc = jw0 + 16 * c + 8 * hh;
-        const uint32_t keep = DROP ? keep_bits8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1, P.thresh) : 0xFFu;
+        Philox4 rnd = {0u, 0u, 0u, 0u};
+        if (DROP) rnd = philox_call8(rowG + (uint64_t)(jc >> 3), 0u, P.key0, P.key1);
         float dvv[8], ds[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -lse2));
-          const float km = ((keep >> e) & 1u) ? P.keep_scale : 0.f;
+          // the 16-bit field compared where it lies (no 8-bit mask in between: 60 fewer vector instructions per step)
+          const float km = (!DROP || keep_field(rnd, e, P.thresh)) ? P.keep_scale : 0.f;
           dvv[e] = pe * km;
           ds[e] = pe * (dd[8 * c + e] * km - dl);
         }
