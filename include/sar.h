@@ -87,7 +87,8 @@ sar_status attn_core_fwd(const sar_attn_desc* desc, const void* q, const void* k
  *     nothing of size s x s is kept from the forward (Section 5).  bf16 with head dimension 64 / 96 / 128 / 160 only.
  *   - workspace_bytes >= attn_core_bwd_workspace_min(desc) (one float per query row): the region is recomputed TWICE, once
  *     per query block for dQ and once per key block for dK, dV; scratch is O(s).
- * attn_core_bwd_workspace returns the first size while it stays below 4 GiB (s = 8192 with 16 heads: 1.1 GB), else the second.
+ * attn_core_bwd_workspace returns the first size while it stays below 8 GiB (16 heads: s = 8192 1.1 GB, s = 16384 4.3 GB,
+ * s = 32768 17 GB), else the second.
  */
 size_t attn_core_bwd_workspace(const sar_attn_desc* desc);
 size_t attn_core_bwd_workspace_min(const sar_attn_desc* desc);

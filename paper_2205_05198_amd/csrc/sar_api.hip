@@ -69,7 +69,7 @@ sar_status check_mfma_limits(const sar::AttnParams& P) {
 // workspace of the backward: delta (one float per row) and, for the path that recomputes the region once, the dS tiles
 size_t delta_bytes(const sar::AttnParams& P) { return ((size_t)P.b * P.A * P.s * sizeof(float) + 255) / 256 * 256; }
 size_t ds_bytes(const sar::AttnParams& P) { return (size_t)P.b * P.A * (size_t)sar::ds_tiles_per_head(P) * sar::kDsTileElems * 2; }
-constexpr size_t kDsWorkspaceCap = 4ull << 30;  // above this attn_core_bwd_workspace asks for the two-pass backward's scratch only
+constexpr size_t kDsWorkspaceCap = 8ull << 30;  // above this attn_core_bwd_workspace asks for the two-pass backward's scratch only
 
 sar_status check_simple_limits(const sar::AttnParams& P) {
   if (sar::attn_simple_lds_bytes(P.s) > 160 * 1024) return fail(SAR_ERR_UNSUPPORTED, "s (%d) too long for this dtype / head dimension", P.s);

@@ -47,6 +47,8 @@ WORKLOADS = {
     # Eq. 6) and the encoder form of the core (no causal mask)
     "530B_s4096": Workload("530B_s4096", "bf16", 4096, 1, 128, 20480, 8, 0.1, 1234, 512, 20480),
     "530B_s8192": Workload("530B_s8192", "bf16", 8192, 1, 128, 20480, 8, 0.1, 1234, 1024, 20480),
+    "530B_s16384": Workload("530B_s16384", "bf16", 16384, 1, 128, 20480, 8, 0.1, 1234, 2048, 20480),
+    "530B_s32768": Workload("530B_s32768", "bf16", 32768, 1, 128, 20480, 8, 0.1, 1234, 4096, 20480),
     "530B_p0": Workload("530B_p0", "bf16", 2048, 1, 128, 20480, 8, 0.0, 1234, 256, 20480),   # no dropout: no random numbers drawn
     "530B_enc": Workload("530B_enc", "bf16", 2048, 1, 128, 20480, 8, 0.1, 1234, 256, 20480, 0),
 }

@@ -334,3 +334,62 @@ def test_stored_baseline_full_size_sampled_head():
         assert np.max(np.abs(got[nm][0, n] - f[nm][0])) <= 2.0 ** -8, nm
     _check_bf16_heads("stored-530B", sh, q, k, v, do, got, (n,))
 
+
+
+def test_sequence_16384_sampled_rows_and_both_backward_forms():
+    """s = 16384 (256 tiles per row block; the oracle would need minutes per head): sampled rows of O, LSE and dQ against the
+    definition written out in fp64 for those rows (row i needs only its own scores), the mask from the oracle's Philox; and
+    the two forms of the backward against each other on every element (same arithmetic, different kernels for dQ)."""
+    import paper_2205_05198_amd as sar
+    import torch
+    from gpu_util import dev, host
+    from paper_2205_05198_amd.binding import SAR_BF16
+    s, d, p = 16384, 160, 0.1
+    sh = oracle.AttnShape(s=s, b=1, a=1, h=d, p=p, seed=1234, offset=3)
+    q, k, v, do = attn_inputs(s, 1, 1, d, "bf16", seed=73)
+    desc = sar.AttnDesc.packed(s, 1, 1, d, dtype=SAR_BF16, p=p, seed=1234, offset=3, scale=sh.alpha())
+    tq, tk, tv, tdo = (dev(x, "bf16") for x in (q, k, v, do))
+    o = torch.empty_like(tq)
+    lse = torch.empty((1, 1, s), dtype=torch.float32, device="cuda")
+    print("bf16 s=16384 one head", flush=True)
+    sar.attn_core_fwd(desc, tq, tk, tv, o, lse)
+    res = {}
+    for form, nbytes in (("once", sar.attn_core_bwd_workspace(desc)), ("twice", sar.attn_core_bwd_workspace_min(desc))):
+        dq, dk, dv = (torch.empty_like(tq) for _ in range(3))
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        sar.attn_core_bwd_recompute(desc, tq, tk, tv, o, lse, tdo, dq, dk, dv, ws)
+        torch.cuda.synchronize()
+        res[form] = {n: host(x)[:, 0, 0] for n, x in (("dq", dq), ("dk", dk), ("dv", dv))}
+        del ws
+    assert sar.attn_core_bwd_workspace(desc) > sar.attn_core_bwd_workspace_min(desc)
+    # the column pass is the same kernel in both forms: dV (which does not involve delta) agrees bit for bit; delta is summed
+    # in a different order by the two forms (fp32), so dK and dQ agree to a rounding of the result
+    assert np.array_equal(res["once"]["dv"], res["twice"]["dv"])
+    for n in ("dk", "dq"):
+        r = float(np.sqrt(np.mean(res["twice"][n] ** 2)))
+        assert np.max(np.abs(res["once"][n] - res["twice"][n]) / (2e-2 * r + 2.0 ** -7 * np.abs(res["twice"][n]))) <= 1.0, n
+    rms = float(np.sqrt(np.mean(res["twice"]["dq"] ** 2)))
+    # sampled rows, fp64
+    Q, K, V, DO = (np.asarray(x[:, 0, 0], dtype=np.float64) for x in (q, k, v, do))
+    O, L = host(o)[:, 0, 0], host(lse)[0, 0]
+    c, T = 1.0 / (1.0 - float(np.float32(p))), oracle.dropout_threshold(p)
+    rows = [0, 1, 63, 64, 1000, 4095, 4096, 8191, 12345, s - 65, s - 1]
+    o_rms, dq_rms = float(np.sqrt(np.mean(O ** 2))), rms
+    for i in rows:
+        sc = sh.alpha() * (K[:i + 1] @ Q[i])
+        m = sc.max()
+        e = np.exp(sc - m)
+        P = e / e.sum()
+        M = np.array([oracle.keep_bit(sh.seed, sh.offset, i * s + j, 0, T) for j in range(i + 1)], dtype=np.float64)
+        D = P * M * c
+        o_ref = D @ V[:i + 1]
+        assert abs(L[i] - (m + np.log(e.sum()))) < 2e-3 * (1 + abs(m)), i
+        assert np.all(np.abs(O[i] - o_ref) <= 2e-2 * o_rms + 2.0 ** -8 * (D @ np.abs(V[:i + 1]) + np.abs(o_ref))), i
+        dP = (V[:i + 1] @ DO[i]) * M * c
+        delta = float(P @ dP)
+        dS = P * (dP - delta)
+        dq_ref = sh.alpha() * (dS @ K[:i + 1])
+        dabs = float(np.abs(DO[i]) @ (D @ np.abs(V[:i + 1])))
+        scale = sh.alpha() * ((P * (np.abs(dP) + dabs)) @ np.abs(K[:i + 1]))
+        for form in ("once", "twice"):
+            assert np.all(np.abs(res[form]["dq"][i] - dq_ref) <= 2e-2 * dq_rms + 2.0 ** -8 * (scale + np.abs(dq_ref))), (form, i)

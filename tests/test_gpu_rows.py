@@ -50,7 +50,7 @@ def test_layernorm(rows, h, dtype):
     for nm in ("mean", "rstd", "dgamma", "dbeta"):
         e = err(got[nm], ref[nm], "f32")
         print(f"  {nm}: {e:.3e}", flush=True)
-        assert e <= (1e-4 if nm in ("mean", "rstd") or dtype == "f32" else 1e-3), nm
+        assert e <= 1e-4, nm
 
 
 def test_layernorm_large_mean():
@@ -61,8 +61,9 @@ def test_layernorm_large_mean():
     inp["x"] = (inp["x"] * 0.5 + 300.0).astype(np.float32)
     got = _run_ln(rows, h, "f32", inp)
     f = oracle.ln_fwd(inp["x"], inp["gamma"], inp["beta"], 1e-5)
-    assert err(got["y"], f["y"], "f32") < 1e-3
-    assert err(got["rstd"], f["rstd"], "f32") < 1e-3
+    e_y, e_r = err(got["y"], f["y"], "f32"), err(got["rstd"], f["rstd"], "f32")
+    print(f"  large mean: y {e_y:.3e} rstd {e_r:.3e}", flush=True)
+    assert e_y < 1e-4 and e_r < 1e-4
 
 
 def _run_bda(rows, h, dtype, inp, p, seed, offset, row_offset=0, bias=True, mask=True, inplace=False):

@@ -117,3 +117,43 @@ def test_attn_core_flops():
     # without the causal discount the forward count is Appendix A's 4 B s^2 h for this GPU's heads
     f2 = acc.attn_core_flops(2048, 1, 16, 160, causal=False)
     assert f2["fwd"] == 4 * 1 * 2048 * 2048 * (16 * 160)
+
+
+def test_first_stage_total_against_section_4_3_items_and_appendix_b():
+    """total_act_bytes_first_stage = L layers of Eq. 5 / Eq. 6 plus the extras that Section 4.3 itemises, checked against
+    the items themselves (not the closed form the function uses) and against the number Appendix B prints."""
+    # p > 1 (530B: p = 35): the only extra is the embedding dropout, sbhp/t bytes.  Appendix B prints sbhp = 2.73 GB at
+    # 2 bytes per element for this model, so the extra is 2.73 GiB / (2 t).
+    m = MODELS["530B"]
+    for sel, per_layer in ((False, acc.act_bytes_tp_sp), (True, acc.act_bytes_tp_sp_selective)):
+        tot = acc.total_act_bytes_first_stage(S, m["b"], m["h"], m["a"], m["L"], 8, m["p"], VOCAB, selective=sel)
+        extra = tot - m["L"] * per_layer(S, m["b"], m["h"], m["a"], 8)
+        assert abs(float(extra) * 2 * 8 / 2 ** 30 - V["out_dealloc_530b_gb"]) < 0.01
+    # p = 1 (22B): besides the embedding dropout (sbh/t), the final LayerNorm input (2sbh/t), the output projection's
+    # input (2sbh/t) and the fp32 logits (4sbv/t), as Section 4.3 lists them one by one
+    m = MODELS["22B"]
+    assert m["p"] == 1
+    s, b, h, t = S, m["b"], m["h"], 8
+    items = Fraction(s * b * h, t) + Fraction(2 * s * b * h, t) + Fraction(2 * s * b * h, t) + Fraction(4 * s * b * VOCAB, t)
+    tot = acc.total_act_bytes_first_stage(s, b, h, m["a"], m["L"], t, 1, VOCAB)
+    assert tot - m["L"] * acc.act_bytes_tp_sp(s, b, h, m["a"], t) == items
+    # the extras are small beside the layers (the section's point; its "0.01 %" does not follow from its own formula)
+    assert float(items / tot) < 0.01
+
+
+def test_the_other_reading_of_eq8_does_not_reproduce_the_printed_overheads():
+    """Eq. 8 as printed adds 12 B L s^2 h; the sentence before it (one more QK^T and attention-over-V per layer) adds
+    4 B L s^2 h.  Only the printed equation gives Section 5's 2.7 % / 1.6 % and Table 5's HFU column; the other reading
+    is kept as hardware_flops_text_reading and is exactly a third of the way from Eq. 7 to Eq. 8."""
+    for key, name in (("gpt3", "175B"), ("mtnlg", "530B")):
+        m = MODELS[name]
+        mf = acc.model_flops(1, m["L"], S, m["h"], VOCAB)
+        hf = acc.hardware_flops(1, m["L"], S, m["h"], VOCAB)
+        tf = acc.hardware_flops_text_reading(1, m["L"], S, m["h"], VOCAB)
+        assert 3 * (tf - mf) == hf - mf
+        assert tf - mf == m["L"] * 4 * S * S * m["h"]                                  # one QK^T + one PV forward per layer, Appendix A's 4 B s^2 h
+        assert abs(100 * (tf / mf - 1) - V[key + "_flops_overhead_pct"]) > 1.0         # 0.9 % / 0.6 %: not what the paper prints
+    m = MODELS["530B"]
+    peak = V["a100_peak_tflops"] * 1e12 * m["gpus"]
+    hfu_text = 100 * acc.hardware_flops_text_reading(m["B"], m["L"], S, m["h"], VOCAB) / m["iter_s"] / peak
+    assert abs(hfu_text - m["hfu"]) > 0.25                                             # Table 5's HFU needs the printed equation
