@@ -175,8 +175,20 @@ def main():
         for i in range(nb):
             step_eager(evs[i])
         torch.cuda.synchronize()
-        kern_ms = {n: float(np.median([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(nb)])) for j, n in enumerate(names)}
-        kern_ms[names[DOM]] = dom_ms
+        # What two consecutive event records cost the stream when nothing lies between them, with kernels before and after
+        # as in a step: an event-bracketed duration contains one such gap.
+        gap_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b_ in gap_ev:
+            calls[DOM - 1]()
+            a.record()
+            b_.record()
+            calls[DOM + 1]()
+        torch.cuda.synchronize()
+        event_gap_ms = float(np.median([a.elapsed_time(b_) for a, b_ in gap_ev]))
+        kern_ms_raw = {n: float(np.median([evs[i][j].elapsed_time(evs[i][j + 1]) for i in range(nb)])) for j, n in enumerate(names)}
+        kern_ms_raw[names[DOM]] = dom_ms
+        kern_ms = {n: max(v - event_gap_ms, 0.0) for n, v in kern_ms_raw.items()}
+        dom_ms_raw, dom_ms = dom_ms, kern_ms[names[DOM]]
         # whole steps without the sampling, for the line's context: graph replays only / host launches only
         def time_steps(fn, n):
             torch.cuda.synchronize()
@@ -297,11 +309,12 @@ def main():
         "pct_mfma_peak": 100.0 * value / PEAK_BF16_MFMA_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic,
-                     "duration_us": dom_ms * 1e3,
-                     "duration_source": f"median of HIP events around the kernel on the launch stream, every {SAMPLE}th step of the timed region",
+                     "duration_us": dom_ms * 1e3, "duration_us_events_raw": dom_ms_raw * 1e3, "event_gap_us": event_gap_ms * 1e3,
+                     "duration_source": f"median of HIP events around the kernel on the launch stream, every {SAMPLE}th step of the timed region, minus the "
+                                        "median of an empty event pair between the same neighbouring kernels (what the two records themselves cost)",
                      "flops_per_launch": flops[dom], "traffic_source": "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run, scaled by a copy of known size); not measured in this run"},
         "cpu_baseline": cpu,
-        "kernels_ms": kern_ms,
+        "kernels_ms": kern_ms, "kernels_ms_events_raw": kern_ms_raw,
         "step_ms": {"timed_region": ms_per_step, "graph_replays_only": ms_graph_only, "host_launches_only": ms_host_launch,
                     "sum_of_kernels": sum(kern_ms.values())},
         "attn_fwd_bwd": {"ms": attn_ms, "tflops_algorithmic_14dTN": flops_alg_fwd_bwd / (attn_ms * 1e-3) / 1e12,
