@@ -118,7 +118,7 @@ def load_library():
         "attn_core_bwd_workspace": (sz, [ad]),
         "attn_core_bwd_workspace_min": (sz, [ad]),
         "attn_core_bwd_recompute_stages": (ctypes.c_int, [ad, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
-        "sar_test_force_variants": (None, [ctypes.c_int, ctypes.c_int, ctypes.c_int]),
+        "sar_test_force_variants": (None, [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]),
         "attn_core_bwd_noalloc_max_bytes": (sz, []),
         "attn_core_bwd_recompute_noalloc": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "attn_core_bwd_recompute": (ctypes.c_int, [ad, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
@@ -206,8 +206,8 @@ def attn_core_bwd_workspace_min(desc: AttnDesc) -> int:
     return int(load_library().attn_core_bwd_workspace_min(ctypes.byref(desc)))
 
 
-def sar_test_force_variants(fwd_128_rows: int = -1, fwd_loader_waves: int = -1, dq_loader_waves: int = -1):
-    load_library().sar_test_force_variants(fwd_128_rows, fwd_loader_waves, dq_loader_waves)
+def sar_test_force_variants(fwd_128_rows: int = -1, fwd_loader_waves: int = -1, dq_loader_waves: int = -1, dkdv_pipelined: int = -1):
+    load_library().sar_test_force_variants(fwd_128_rows, fwd_loader_waves, dq_loader_waves, dkdv_pipelined)
 
 
 def attn_core_bwd_recompute_stages(desc: AttnDesc, stages: int, q, k, v, o, lse, d_o, dq, dk, dv, workspace):

@@ -161,8 +161,9 @@ size_t attn_core_bwd_workspace(const sar_attn_desc* desc) {
   return delta_bytes(P);
 }
 
-void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves) {
+void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves, int dkdv_pipelined) {
   sar::attn_mfma_force_variants(fwd_128_rows, fwd_loader_waves, dq_loader_waves);
+  sar::attn_mfma_force_dkdv_pipelined(dkdv_pipelined);
 }
 
 // passes: two-pass backward, bit 0 = row pass, bit 1 = column pass.  stages (passes == 0): the backward that recomputes the

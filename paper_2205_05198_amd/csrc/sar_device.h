@@ -62,6 +62,22 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
   Philox4 o = {c0, c1, c2, c3};
   return o;
 }
+// The same generator one round at a time, for kernels that spread a call's ten rounds between other instructions.
+// Round r (0 .. 9) uses the key (k0 + r * 0x9E3779B9, k1 + r * 0xBB67AE85).
+__device__ __forceinline__ Philox4 philox_start(uint64_t G, uint32_t site) {
+  Philox4 s = {(uint32_t)G, (uint32_t)(G >> 32), 0u, site};
+  return s;
+}
+__device__ __forceinline__ void philox_round(Philox4& s, uint32_t k0, uint32_t k1, int r) {
+  const uint64_t p0 = (uint64_t)0xD2511F53u * s.x;
+  const uint64_t p1 = (uint64_t)0xCD9E8D57u * s.z;
+  const uint32_t n0 = xor3((uint32_t)(p1 >> 32), s.y, k0 + (uint32_t)r * 0x9E3779B9u);
+  const uint32_t n2 = xor3((uint32_t)(p0 >> 32), s.w, k1 + (uint32_t)r * 0xBB67AE85u);
+  s.y = (uint32_t)p1;
+  s.w = (uint32_t)p0;
+  s.x = n0;
+  s.z = n2;
+}
 // the eight 16-bit fields of one call, for elements 8G .. 8G+7, as keep bits (bit r set = element r kept)
 __device__ __forceinline__ uint32_t keep_bits8(uint64_t G, uint32_t site, uint32_t k0, uint32_t k1, uint32_t T) {
   Philox4 o = philox4x32_10((uint32_t)G, (uint32_t)(G >> 32), 0u, site, k0, k1);

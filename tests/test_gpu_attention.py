@@ -36,9 +36,9 @@ def _oracle(sh, q, k, v, do, heads=None):
 def _library_picks_variants():
     """Every test starts and ends with the library choosing its kernel variants."""
     import paper_2205_05198_amd as sar
-    sar.sar_test_force_variants(-1, -1, -1)
+    sar.sar_test_force_variants(-1, -1, -1, -1)
     yield
-    sar.sar_test_force_variants(-1, -1, -1)
+    sar.sar_test_force_variants(-1, -1, -1, -1)
 
 
 def _check_bf16_heads(tag, sh, q, k, v, do, got, heads, peaked=False):
@@ -181,7 +181,7 @@ def test_random_shapes_and_kernel_variants():
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = [rng.choice([-1, 0, 1]) for _ in range(3)]
+        env = [rng.choice([-1, 0, 1]) for _ in range(4)]
         if s < 128:
             env[0] = -1
         sar.sar_test_force_variants(*env)
@@ -191,6 +191,23 @@ def test_random_shapes_and_kernel_variants():
         print(f"case {case}: d={d} s={s} b={b} A={A} t={t} rank={rank} p={p} causal={causal} variants={env} two_pass={two_pass}", flush=True)
         got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
         _check_bf16_heads(f"sweep{case}", sh, q, k, v, do, got, range(b * A))
+
+
+@pytest.mark.parametrize("pipe", [0, 1])
+@pytest.mark.parametrize("two_pass", [False, True])
+@pytest.mark.parametrize("d,s,b,A,p,causal", [(160, 320, 1, 2, 0.1, 1), (128, 256, 2, 1, 0.25, 1), (160, 192, 1, 2, 0.1, 0), (128, 64, 1, 2, 0.0, 1), (160, 128, 1, 1, 0.0, 0)])
+def test_column_pass_pipelined_and_plain(d, s, b, A, p, causal, two_pass, pipe):
+    """The column pass in its software-pipelined form (three query-tile stages, K operands in registers) and in its plain
+    form, both forced, on sequences of one to five full tiles: with and without the mask, with and without dropout, in
+    both forms of the backward."""
+    import paper_2205_05198_amd as sar
+    from gpu_util import run_attn
+    sar.sar_test_force_variants(-1, -1, -1, pipe)
+    sh = oracle.AttnShape(s=s, b=b, a=A * 2, h=A * 2 * d, t=2, rank=1, p=p, seed=77, offset=(1 << 32) - 1000, causal=causal)
+    q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=29)
+    print(f"column pass pipelined={pipe} d={d} s={s} causal={causal} p={p} two_pass={two_pass}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
+    _check_bf16_heads(f"cols-pipe{pipe}", sh, q, k, v, do, got, range(b * A))
 
 
 def test_bf16_generic_path_other_head_dim():

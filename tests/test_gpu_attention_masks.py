@@ -103,17 +103,26 @@ def test_fused_kernel_masks_small(d, s, causal):
         _compare(sh, "dq", two_pass)
 
 
-def test_fused_kernel_masks_forward_variants():
-    """The forward's other variants (128-row workgroups; without loader waves) draw the same mask."""
+def test_fused_kernel_masks_kernel_variants():
+    """The forward's other variants (128-row workgroups; without loader waves) and both forms of the column pass draw the same mask."""
     sh = oracle.AttnShape(s=328, b=1, a=4, h=4 * 160, t=2, rank=1, p=0.25, seed=99, offset=12345)
     try:
-        for variant in ((1, -1, -1), (0, 0, 0), (0, 1, 1)):
+        for variant in ((1, -1, -1, -1), (0, 0, 0, -1), (0, 1, 1, -1)):
             sar.sar_test_force_variants(*variant)
             print(f"masks variants={variant}", flush=True)
             _compare(sh, "fwd")
             _compare(sh, "dq", two_pass=True)
+        # the column pass, pipelined and plain, at a length of full tiles (s % 64 == 0), both head dimensions it exists for
+        for d in (128, 160):
+            sh2 = oracle.AttnShape(s=320, b=1, a=4, h=4 * d, t=2, rank=1, p=0.25, seed=99, offset=(1 << 32) - 4000)
+            for pipe in (0, 1):
+                sar.sar_test_force_variants(-1, -1, -1, pipe)
+                print(f"masks column pass pipelined={pipe} d={d}", flush=True)
+                for two_pass in (False, True):
+                    _compare(sh2, "dv", two_pass)
+                    _compare(sh2, "dq", two_pass)
     finally:
-        sar.sar_test_force_variants(-1, -1, -1)
+        sar.sar_test_force_variants(-1, -1, -1, -1)
 
 
 def test_fused_kernel_masks_530B_shard():
@@ -134,3 +143,17 @@ def test_fused_kernel_masks_530B_shard():
     _compare(sh, "dq")
     _compare(sh, "dv", two_pass=True)
     _compare(sh, "dq", two_pass=True)
+
+
+def test_fused_kernel_masks_175B_shard_pipelined_column_pass():
+    """The 175B shard (s = 2048, 12 heads of 128), where the library picks the software-pipelined column pass: its mask and the
+    mask inside the dS tiles it stores, every head, low counter word overflowing inside head 5."""
+    s, a, t, rank, d = 2048, 96, 8, 6, 128
+    A = a // t
+    first = (rank * A) * s * s // 8
+    per_head = s * s // 8
+    offset = (1 << 32) - first - 5 * per_head - per_head // 7
+    sh = oracle.AttnShape(s=s, b=1, a=a, h=a * d, t=t, rank=rank, p=0.1, seed=4321, offset=offset)
+    print("masks 175B shard", flush=True)
+    _compare(sh, "dv")
+    _compare(sh, "dq")
