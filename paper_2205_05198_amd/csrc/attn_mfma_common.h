@@ -27,6 +27,13 @@ __device__ __forceinline__ bf16x8_t pack8(const float* f) {
   return u.v;
 }
 
+// max of a value with the one held 32 lanes away (v_permlane32_swap exchanges the upper half of one register with the lower
+// half of the other: afterwards one holds the lower half's values in both halves, the other the upper half's)
+__device__ __forceinline__ float xhalf_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // LDS row that holds row r (0..63) of a K tile: bits 2 and 3 swapped inside each group of 32 rows
 __device__ __forceinline__ int perm_row(int r) { return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1); }
 

@@ -36,11 +36,14 @@ static constexpr float kLazyRescale = 60.0f;  // the running reference exponent 
 // serves twice the rows (half the tile bytes through the L1 per unit of work); under the causal mask the two lower
 // row groups stop one tile before the two upper ones.
 // K and V tiles (both with swapped rows) go from global memory straight into LDS, two stages each.
-// The score tile runs one step ahead of the rest: step j computes S_{j+1} (matrix core + LDS reads) in the same
-// basic block as the softmax / dropout arithmetic of tile j and the product P_j V_j, so that the
-// instruction scheduler can overlap the three.  Everything that needs a branch sits at the ends of a step: the
-// causal mask only exists in the variants of the step that produce the diagonal tile, and the (rare) rescaling
-// of the running maximum for tile j+1 is decided at the end of step j.
+// The score tile and the Philox words run one step ahead of the rest: step j computes S_{j+1} between the exponentials and
+// keep decisions of tile j, then P_j V_j between the Philox rounds, the mask and the row maximum of tile j+1 (the order
+// is laid out by hand, see the step).  A wave issues in order, so a step costs the sum of its instructions' issue times
+// whichever pipe executes them: measured at d = 160 per 64 x 64 step, 1700 cycles = ~1130 of vector instructions
+// (16 exponentials at quarter rate are 256 of them, two Philox calls 320) + ~240 for issuing 20 matrix instructions +
+// ~260 for 30 LDS reads + ~80 at the barrier; with the vector work removed the first half takes 562 cycles, with the
+// matrix work and its reads removed 627, both together 946.  The (rare) rescaling of the running maximum for tile j+1
+// is decided at the end of step j.
 // ===================================================================================================
 // DROP = false is the p = 0 variant: no random numbers are drawn at all.
 // LW (64-row workgroups only): four more waves, one per SIMD, that do nothing but fetch the K / V tiles.  A wave-wide
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
 #pragma unroll
     for (int e = 3; e < 15; e += 2) mt = fmaxf(fmaxf(mt, st[e]), st[e + 1]);
     mt = fmaxf(mt, st[15]);
-    return fmaxf(fmaxf(mt, __shfl_xor(mt, 32, 64)) * sc2, -1.0e30f);
+    return fmaxf(xhalf_max(mt) * sc2, -1.0e30f);
   };
 
   if constexpr (!LW) {
@@ -169,46 +172,102 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
   float16_t st = nt_w == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
   float m_ref = tile_max(st);
 
-  // One step: tile jt's softmax, dropout and P V, and (NEXT != 0) the scores of tile jt+1; NEXT == 2: that tile is
-  // the diagonal one.
+  // Philox words of the tile whose probabilities are formed next: rnd[c] covers this lane's keys 16 c + 8 hh .. + 7 of
+  // its wave's half of the tile.  They do not depend on the scores, so they are drawn one step ahead.
+  Philox4 rnd[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+  auto philox_begin = [&](Philox4 (&r)[2], const int jt) __attribute__((always_inline)) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) r[c] = philox_start(rowG + (uint64_t)((jt * BN + 32 * ks + 16 * c + 8 * hh) >> 3), 0u);
+  };
+  if (DROP) {
+    philox_begin(rnd, 0);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+      philox_round(rnd[0], P.key0, P.key1, r);
+      philox_round(rnd[1], P.key0, P.key1, r);
+    }
+  }
+
+  // One step, laid out by hand in two halves so that the matrix pipe and the vector pipe of the SIMD run side by side
+  // (the scheduler left to itself puts most of the vector work between the two groups of matrix instructions):
+  //   first half : the KC matrix instructions of the scores of tile jt+1 (K operands read kAhead instructions ahead), and
+  //                between them tile jt's exponentials, keep decisions and sums, dealt out evenly;
+  //   second half: the 2 DT matrix instructions of O^T += V^T P^T for tile jt (V^T operands read kAhead ahead), and
+  //                between them the twenty Philox rounds (two calls) of tile jt+1.
+  // NEXT != 0: there is a tile jt+1; NEXT == 2: it is the diagonal one.
   auto step = [&](const int jt, auto next) __attribute__((always_inline)) {
     constexpr int NEXT = decltype(next)::value;
+    constexpr int kAhead = 3, NPV = 2 * DT;
     if constexpr (!LW) dma_wait();  // this wave's loads of K tile jt+1 and V tile jt have landed
     __syncthreads();                // ... and everybody's; nobody reads K tile jt or V tile jt-1 any more
     if constexpr (!LW) {
       if (jt + 2 < ntile) load_tile(kg, Kst, jt + 2);
       if (jt + 1 < ntile) load_tile(vg, Vst, jt + 1);
     }
+    const uint16_t* Ksn = Kst + ((jt + 1) & 1) * TILE + (32 * ks + li) * KP + 8 * hh;
     const uint16_t* Vs = Vst + (jt & 1) * TILE;
-    const int j0w = jt * BN + 32 * ks;
     float16_t stn;
-    if (NEXT == 1) stn = scores(jt + 1, std::false_type{});
-    if (NEXT == 2) stn = scores(jt + 1, std::true_type{});
+#pragma unroll
+    for (int e = 0; e < 16; ++e) stn[e] = 0.f;
+    bf16x8_t kfr[kAhead], vfr[kAhead];
+    if (NEXT != 0) {
+#pragma unroll
+      for (int a = 0; a < kAhead && a < KC; ++a) kfr[a] = ld_frag(Ksn + 16 * a);
+    }
+    auto v_frag = [&](const int idx) __attribute__((always_inline)) {
+      return ld_frag_tr_perm(Vs, KP, 32 * ks + 16 * (idx / DT), 32 * (idx % DT), lane);
+    };
     float psum = 0.f;
-    bf16x8_t pf[2];
+    float pd[16];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      Philox4 rnd = {0u, 0u, 0u, 0u};
-      if (DROP) rnd = philox_call8(rowG + (uint64_t)((j0w + 16 * c + 8 * hh) >> 3), 0u, P.key0, P.key1);
-      float pd[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float pe = __builtin_amdgcn_exp2f(fmaf(st[8 * c + e], sc2, -m_ref));
-        psum += pe;
-        pd[e] = (!DROP || keep_field(rnd, e, P.thresh)) ? pe : 0.f;
+    for (int kc = 0; kc < KC; ++kc) {
+      if (NEXT != 0) {
+        stn = mfma32(kfr[kc % kAhead], qf[kc], stn);
+        if (kc + kAhead < KC) kfr[kc % kAhead] = ld_frag(Ksn + 16 * (kc + kAhead));
       }
-      pf[c] = pack8(pd);
+      if (kc >= KC - kAhead && kc - (KC - kAhead) < NPV) vfr[kc - (KC - kAhead)] = v_frag(kc - (KC - kAhead));
+#pragma unroll
+      for (int e = (16 * kc) / KC; e < (16 * (kc + 1)) / KC; ++e) {
+        const float pe = __builtin_amdgcn_exp2f(fmaf(st[e], sc2, -m_ref));
+        psum += pe;
+        pd[e] = (!DROP || keep_field(rnd[e >> 3], e & 7, P.thresh)) ? pe : 0.f;
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
     l_run += psum;
-    // ---- O^T += V^T P^T ----
+    bf16x8_t pf[2];
+    pf[0] = pack8(pd);
+    pf[1] = pack8(pd + 8);
+    Philox4 rn[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+    if (DROP && NEXT != 0) philox_begin(rn, jt + 1);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- O^T += V^T P^T; beside it the next tile's mask, maximum and Philox rounds ----
+    float mt = 0.f;
 #pragma unroll
-    for (int c = 0; c < 2; ++c)
+    for (int idx = 0; idx < NPV; ++idx) {
+      oacc[idx % DT] = mfma32(vfr[idx % kAhead], pf[idx / DT], oacc[idx % DT]);
+      if (idx + kAhead < NPV) vfr[idx % kAhead] = v_frag(idx + kAhead);
+      if (NEXT == 2 && idx == 1) {  // the diagonal tile: keys beyond jlim are masked
+        const int j0n = (jt + 1) * BN + 32 * ks;
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) oacc[dt] = mfma32(ld_frag_tr_perm(Vs, KP, 32 * ks + 16 * c, 32 * dt, lane), pf[c], oacc[dt]);
+        for (int e = 0; e < 16; ++e)
+          if (j0n + 16 * (e >> 3) + 8 * hh + (e & 7) > jlim) stn[e] = -INFINITY;
+      }
+      if (NEXT != 0 && idx == 2) mt = tile_max(stn);
+      if (DROP && NEXT != 0) {
+#pragma unroll
+        for (int u = (20 * idx) / NPV; u < (20 * (idx + 1)) / NPV; ++u) philox_round(rn[u & 1], P.key0, P.key1, u >> 1);
+        // the words are next needed in the following step: without a use here the rounds sink below the matrix instructions
+#pragma unroll
+        for (int c = 0; c < 2; ++c) asm volatile("" : "+v"(rn[c].x), "+v"(rn[c].y), "+v"(rn[c].z), "+v"(rn[c].w));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (NEXT != 0) {
       st = stn;
+      rnd[0] = rn[0];
+      rnd[1] = rn[1];
       // the running reference exponent only moves when the next tile's maximum exceeds it by more than 2^60
-      const float mt = tile_max(stn);
       if (__builtin_expect(__builtin_amdgcn_ballot_w64(mt > m_ref + kLazyRescale) != 0, 0)) {
         const float m_new = fmaxf(m_ref, mt);
         const float corr = __builtin_amdgcn_exp2f(m_ref - m_new);
