@@ -47,20 +47,23 @@ __global__ __launch_bounds__(256) void attn_bwd_delta_kernel(AttnParams P, const
 // ---------------------------------------------------------------------------------------------------
 // dQ = alpha dS K.  Workgroup = 64 query rows: 4 computing waves = 2 row groups x 2 key halves of each 64-key tile (summed
 // through LDS at the end, as in the row pass of the two-pass backward) and 4 waves, one per SIMD, that only fetch the K
-// tiles (rows swapped inside groups of 32, see attn_mfma_rows.hip) global -> LDS, three stages, two tiles ahead.
+// tiles (rows swapped inside groups of 32, see attn_mfma_rows.hip) global -> LDS in pairs (one barrier per two tiles: the fixed cost of a barrier-to-barrier section, about 600 cycles
+// beside 320 of matrix work per tile, is paid half as often), three stages of a pair each, two pairs ahead.
 // The dS operand of a computing wave is 16 bytes per lane and 16-key group, read straight from the tile in the order
 // the column pass wrote it, kDsAhead tiles ahead: the pass does little arithmetic per byte, so what bounds it is how many
 // bytes a CU keeps in flight.  The computing waves issue no direct-to-LDS loads, so the compiler's own bookkeeping of
 // their outstanding loads is exact and each step waits for its own operands only.
 // ---------------------------------------------------------------------------------------------------
-static constexpr int kDsAhead = 6;
+static constexpr int kDsAhead = 6;  // even: a round of the register ring is a whole number of tile pairs
 
 template <int D>
 __global__ __launch_bounds__(512, 1) void attn_bwd_dq_gemm_kernel(AttnParams P, const uint16_t* __restrict__ k, const uint16_t* __restrict__ ds_ws,
                                                                  uint16_t* __restrict__ dq) {
   constexpr int BM = 64, BN = 64, KP = D + 8, DT = D / 32, NS = 3;
   constexpr int TILE = BN * KP;
-  __shared__ __attribute__((aligned(16))) uint16_t smem[NS * TILE];  // K stages; afterwards the exchange buffers, then the output tile
+  // K stages of two tiles each (one barrier per pair of tiles); afterwards the exchange buffers, then the output tile
+  __shared__ __attribute__((aligned(16))) uint16_t smem[NS * 2 * TILE];
+  auto stage = [&](int jt) __attribute__((always_inline)) { return smem + (((jt >> 1) % NS) * 2 + (jt & 1)) * TILE; };
 
   const int N = P.b * P.A;
   const int nrb = (P.s + BM - 1) / BM;
@@ -77,19 +80,21 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_gemm_kernel(AttnParams P, 
     map.init(lw, lane, gstride, true);
     auto fetch = [&](int jt) __attribute__((always_inline)) {
       const int left = P.s - jt * BN;
-      uint16_t* st2 = smem + (jt % NS) * TILE;
+      uint16_t* st2 = stage(jt);
       if (left >= BN) dma_tile<D>(map, kg + (int64_t)(jt * BN) * gstride, st2, lw);
       else dma_tile_ragged<D>(map, kg + (int64_t)(jt * BN) * gstride, st2, lw, lane, gstride, left);
     };
-    fetch(0);
-    if (ntile > 1) fetch(1);
-    for (int jt = 0; jt < ntile; ++jt) {
-      // tile jt has landed; the loads of tile jt + 1 (at least DmaMap::PER - 1 per wave) may still be in flight
-      if (jt + 1 < ntile) dma_wait_keep<DmaMap<D>::PER - 1>();
+    for (int jt = 0; jt < 4 && jt < ntile; ++jt) fetch(jt);  // pairs 0 and 1
+    for (int jt = 0; jt < ntile; jt += 2) {
+      // the pair (jt, jt + 1) has landed; the loads of the next pair (at least DmaMap::PER - 1 per wave and tile) may
+      // still be in flight
+      const int later = ntile - (jt + 2);
+      if (later >= 2) dma_wait_keep<2 * (DmaMap<D>::PER - 1)>();
+      else if (later == 1) dma_wait_keep<DmaMap<D>::PER - 1>();
       else dma_wait();
-      __syncthreads();  // top of step jt: tile jt is there, and nobody reads tile jt - 1 (whose stage tile jt + 2 takes) any more
-      if (jt + 2 < ntile) fetch(jt + 2);
-
+      __syncthreads();  // top of the pair: its tiles are there, and nobody reads the pair before it (whose stage the pair after next takes) any more
+      if (jt + 4 < ntile) fetch(jt + 4);
+      if (jt + 5 < ntile) fetch(jt + 5);
     }
     __syncthreads();  // the four barriers of the others' epilogue
     __syncthreads();
@@ -117,7 +122,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_gemm_kernel(AttnParams P, 
       d0 = __builtin_bit_cast(bf16x8_t, zero);
       d1 = __builtin_bit_cast(bf16x8_t, zero);
     }
-    const uint16_t* Ks = smem + (jt % NS) * TILE;
+    const uint16_t* Ks = stage(jt);
     constexpr int kAhead = 3, NF = 2 * DT;
     bf16x8_t fr[kAhead];
 #pragma unroll
@@ -145,7 +150,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_gemm_kernel(AttnParams P, 
   for (; jt0 + kDsAhead <= ntile; jt0 += kDsAhead) {
 #pragma unroll
     for (int u = 0; u < kDsAhead; ++u) {
-      __syncthreads();  // K tile jt0 + u is in its stage
+      if ((u & 1) == 0) __syncthreads();  // K tiles jt0 + u and jt0 + u + 1 are in their stage
       step(jt0 + u, ring[u][0], ring[u][1]);
       // refilled only now, when its last reader has been issued: the new load can then land in the same registers (loaded
       // at the top of the step it needs registers of its own, and the compiler moves every slot's value, load waited
@@ -158,7 +163,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dq_gemm_kernel(AttnParams P, 
 #pragma unroll
   for (int u = 0; u < kDsAhead - 1; ++u)
     if (jt0 + u < ntile) {
-      __syncthreads();
+      if ((u & 1) == 0) __syncthreads();
       step(jt0 + u, ring[u][0], ring[u][1]);
     }
   // ---- sum the two key halves, scale, store ----
