@@ -53,14 +53,16 @@ __device__ __forceinline__ int perm_row(int r) { return (r & ~12) | ((r & 4) << 
 typedef __attribute__((address_space(3))) void lds_void_t;
 
 __device__ __forceinline__ uint32_t lds_addr(const void* p) { return (uint32_t)(uintptr_t)(lds_void_t*)p; }
-__device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gaddr), "s"(lds_base) : "m0");
+// The global address is a wave-uniform base (the tile's first row, in scalar registers) plus this lane's 32-bit byte
+// offset: no 64-bit vector addition per load.
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t goff, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(goff), "s"(gbase), "s"(lds_base) : "m0");
 }
 // Same, pinned in the instruction stream: issued after `token` has been computed and before anything that uses
 // `token` afterwards (the statement pretends to modify it).
 template <typename T>
-__device__ __forceinline__ void dma16(const void* gaddr, uint32_t lds_base, T& token) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : "+v"(token) : "v"(gaddr), "s"(lds_base) : "m0");
+__device__ __forceinline__ void dma16(const void* gbase, uint32_t goff, uint32_t lds_base, T& token) {
+  asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : "+v"(token) : "v"(goff), "s"(gbase), "s"(lds_base) : "m0");
 }
 // 4 bytes per lane: lane L writes at (LDS base) + 4 L (per-row statistics of a tile: one float per row)
 __device__ __forceinline__ void dma4(const void* gaddr, uint32_t lds_base) {
@@ -101,7 +103,7 @@ template <int D, int NW>
 __device__ __forceinline__ void dma_one(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave, int u) {
   const int l = wave + NW * u;
   if (u < DmaMap<D, NW>::PER - 1 || l < DmaMap<D, NW>::NL)  // only the last round can run past the tile
-    dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l);
+    dma16(gtile, map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l);
 }
 template <int D, int NW>
 __device__ __forceinline__ void dma_tile(const DmaMap<D, NW>& map, const uint16_t* gtile, uint16_t* lds, int wave) {
@@ -114,7 +116,7 @@ __device__ __forceinline__ void dma_tile(const DmaMap<D, NW>& map, const uint16_
   for (int u = 0; u < DmaMap<D, NW>::PER; ++u) {
     const int l = wave + NW * u;
     if (u < DmaMap<D, NW>::PER - 1 || l < DmaMap<D, NW>::NL)
-      dma16(reinterpret_cast<const char*>(gtile) + map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l, token);
+      dma16(gtile, map.goff[u], lds_addr(lds) + 1024u * (uint32_t)l, token);
   }
 }
 // the same for a tile that ends before its 64th row: offsets recomputed with clamped rows
