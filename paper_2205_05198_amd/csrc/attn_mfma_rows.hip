@@ -166,14 +166,10 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
     load_tile(kg, Kst, 0);
     load_tile(vg, Vst, 0);
     if (ntile > 1) load_tile(kg, Kst, 1);
-    dma_wait();
   }
-  __syncthreads();
-  float16_t st = nt_w == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
-  float m_ref = tile_max(st);
-
   // Philox words of the tile whose probabilities are formed next: rnd[c] covers this lane's keys 16 c + 8 hh .. + 7 of
-  // its wave's half of the tile.  They do not depend on the scores, so they are drawn one step ahead.
+  // its wave's half of the tile.  They do not depend on the scores, so they are drawn one step ahead (the first tile's while the first K / V tiles are on
+  // their way).
   Philox4 rnd[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
   auto philox_begin = [&](Philox4 (&r)[2], const int jt) __attribute__((always_inline)) {
 #pragma unroll
@@ -187,6 +183,11 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
       philox_round(rnd[1], P.key0, P.key1, r);
     }
   }
+
+  if constexpr (!LW) dma_wait();
+  __syncthreads();
+  float16_t st = nt_w == 1 ? scores(0, std::true_type{}) : scores(0, std::false_type{});
+  float m_ref = tile_max(st);
 
   // One step, laid out by hand in two halves so that the matrix pipe and the vector pipe of the SIMD run side by side
   // (the scheduler left to itself puts most of the vector work between the two groups of matrix instructions):
