@@ -267,8 +267,9 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
  *   fwd_128_rows      forward with 128 instead of 64 query rows per workgroup (needs s >= 128)
  *   fwd_loader_waves  forward with four extra waves that only fetch K / V tiles
  *   dq_loader_waves   the same for the row pass of the recompute-twice backward
- *   dkdv_pipelined    column pass in its software-pipelined form (score tiles of the next query tile computed beside this
- *                     tile's vector arithmetic); exists for head dimension 128 and 160 and s % 64 == 0, chosen at 128
+ *   dkdv_pipelined    form of the column pass, for head dimension 128 and 160 and s % 64 == 0: 0 plain; 1 software-pipelined
+ *                     (score tiles of the next query tile computed beside this tile's vector arithmetic); 2 producer /
+ *                     consumer (two waves per SIMD: one computes scores, softmax, mask and dS, the other accumulates dK, dV)
  * Process-wide; not meant to be changed while another thread launches.
  */
 void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves, int dkdv_pipelined);

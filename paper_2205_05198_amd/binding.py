@@ -23,6 +23,7 @@ _SOURCES = {
     "attn_mfma_rows.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-mllvm", "-amdgpu-sched-strategy=iterative-ilp"],
     "attn_mfma_cols.hip": [],
     "attn_mfma_cols_small.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+    "attn_mfma_cols_split.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "attn_mfma_stored.hip": [],
     "attn_mfma_dsgemm.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
     "rows.hip": [],

@@ -7,21 +7,43 @@
 
 namespace sar {
 
-static std::atomic<int> g_force_pipe{-1};
-void attn_mfma_force_dkdv_pipelined(int force) { g_force_pipe = force; }
+// form of the column pass at d = 128, 160 and s % 64 == 0: -1 = the library's choice; 0 plain, 1 software-pipelined,
+// 2 producer / consumer waves (forced forms fall back to the plain one where they do not exist)
+static std::atomic<int> g_force_form{-1};
+void attn_mfma_force_dkdv_pipelined(int force) { g_force_form = force; }
 
 hipError_t launch_attn_bwd_dkdv_mfma_small(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
                                            const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);  // attn_mfma_cols_small.hip
+hipError_t launch_attn_bwd_dkdv_mfma_split(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
+                                           const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);  // attn_mfma_cols_split.hip
+
+// the form that runs: 0 plain, 1 software-pipelined, 2 producer / consumer
+template <int D>
+static int dkdv_form(const AttnParams& P) {
+  if (D < 128 || P.s % 64 != 0) return 0;
+  const int force = g_force_form.load();
+  if (force >= 0) return force;
+  // measured (once-form, us): 530B shard 78.6 / 80.2 / 69.6, 175B 70.4 / 60.5 / 48.1, 1T 98.3 / - / 90.0 for forms 0 / 1 / 2
+  return 2;
+}
 
 hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
                                      const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
   switch (P.d) {
     case 64:
     case 96: return launch_attn_bwd_dkdv_mfma_small(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
-    case 128: return bwd_dkdv_use_pipe<128>(P, g_force_pipe.load()) ? bwd_dkdv_pipe_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st)
-                                               : bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
-    case 160: return bwd_dkdv_use_pipe<160>(P, g_force_pipe.load()) ? bwd_dkdv_pipe_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st)
-                                               : bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    case 128:
+      switch (dkdv_form<128>(P)) {
+        case 2: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        case 1: return bwd_dkdv_pipe_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        default: return bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+      }
+    case 160:
+      switch (dkdv_form<160>(P)) {
+        case 2: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        case 1: return bwd_dkdv_pipe_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        default: return bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+      }
     default: return hipErrorInvalidValue;
   }
 }

@@ -1,0 +1,277 @@
+// bf16 attention core, backward column pass (dK, dV) in its two-waves-per-SIMD form: the work of a (32 keys x 32 query rows)
+// block of every step is divided between a producing and a consuming wave that share a SIMD.
+//
+// Why: a wave issues its instructions in order, so with one wave per SIMD a step of the column pass costs the sum of the issue
+// times of its vector instructions, matrix instructions, LDS reads and direct-to-LDS loads (about 3700 cycles at d = 160 for
+// 1400 cycles of matrix-pipe time and 1650 of vector-unit time), and a second wave of the same kind does not fit the register
+// file (two accumulator sets of d/32 x 16 registers plus the arithmetic's working set).  Divided in two, each half fits 256
+// registers, and the halves use different units:
+//   producer (waves 0..3)  S^T = K Q^T and dD^T = V dO^T with K and V operands held in registers, then the vector arithmetic:
+//                          P = exp2(alpha log2e S - LSE), Philox mask, D = M P / (1-p), dS = P (dD M / (1-p) - delta); the two
+//                          results go, rounded to bf16 and one query row per lane, to an exchange buffer in LDS (and, WDS, dS to
+//                          the tiles that the dQ product reads);
+//   consumer (waves 4..7)  moves them to the one-key-per-lane layout (identity matrix instructions), accumulates
+//                          dV^T += dO^T D and dK^T += Q^T dS, and issues every direct-to-LDS load of the workgroup.
+// The consumer works one tile behind the producer; (Q, dO) tiles live in three stages: tile m is loaded during step m-1, read
+// by the producer in step m and by the consumer in step m+1.  One workgroup barrier per step.
+// Needs s % 64 == 0.  Everything is in vector registers (compiled with -amdgpu-mfma-vgpr-form): no copies out of
+// accumulation registers.
+#pragma once
+#include "attn_mfma_cols_kernel.h"
+
+namespace sar {
+
+template <int D, bool DROP, bool WDS>
+__global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                                                                    const uint16_t* __restrict__ v, const float* __restrict__ lse,
+                                                                    const uint16_t* __restrict__ dO, const float* __restrict__ delta,
+                                                                    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, uint16_t* __restrict__ ds_ws) {
+  constexpr int BN = 64, BI = 64, KP = D + 8, KC = D / 16, DT = D / 32, NST = 3;
+  constexpr int TILE = 64 * KP;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[2 * NST * TILE];  // stage s: Q at 2 s TILE, dO at (2 s + 1) TILE; afterwards the epilogue's buffers
+  __shared__ __attribute__((aligned(16))) uint16_t xb[2][4][4][512];      // exchange: [step parity][wave pair][D c0, D c1, dS c0, dS c1][16 bytes per lane]
+  __shared__ float lse_s[NST][BI], delta_s[NST][BI];
+
+  const int N = P.b * P.A;
+  const int kb = (int)(blockIdx.x / N);  // key block 0 sweeps the most rows: heaviest first
+  const int bn = blockIdx.x % N, beta = bn / P.A, n = bn % P.A;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  const bool producer = wave < 4;
+  const int w = wave & 3;  // the pair: waves w and w + 4 sit on SIMD w
+  const int kgp = w & 1, is = w >> 1;
+  const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
+  const int gstride = (int)P.stride_s;
+  const int jw0 = kb * BN + kgp * 32;  // first key of this pair
+  const int nit = P.s / BI;
+  const int it0 = P.causal ? kb : 0;
+  const uint16_t* qg = q + base;
+  const uint16_t* dog = dO + base;
+
+  if (producer) {
+    // ---- K and V operands of this wave's 32 keys, for the whole kernel: lane li holds key jw0 + perm_row(li) ----
+    bf16x8_t kf[KC], vf[KC];
+    {
+      const int64_t row = base + (int64_t)(jw0 + perm_row(li)) * P.stride_s + 8 * hh;
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        kf[kc] = ld_frag(k + row + 16 * kc);
+        vf[kc] = ld_frag(v + row + 16 * kc);
+      }
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(kf[kc]), "+v"(vf[kc]));
+    }
+    const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
+    const float sc2 = P.scale * kLog2e;
+    uint16_t* ds_tile = nullptr;  // uniform: the wave's 2 KB of the dS tile (it, kb)
+    int64_t ds_step = 0;
+    if constexpr (WDS) {
+      ds_tile = ds_ws + ((int64_t)bn * ds_tiles_per_head(P) + ds_tile_index(P, it0, kb)) * kDsTileElems + (2 * is + kgp) * 1024;
+      ds_step = (P.causal ? (int64_t)(it0 + 1) : (int64_t)nit) * kDsTileElems;
+    }
+    for (int m = it0; m <= nit; ++m) {
+      __syncthreads();  // tile m is in its stage; the consumer has read exchange buffer m & 1 (tile m - 2)
+      if (m == nit) break;
+      const uint16_t* Qs = smem + (m % NST) * 2 * TILE;
+      const uint16_t* qrow = Qs + (32 * is + li) * KP + 8 * hh;
+      const uint16_t* drow = qrow + TILE;
+      float16_t st, dd;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
+      const int i = m * BI + 32 * is + li;
+      const float lse2 = lse_s[m % NST][32 * is + li] * kLog2e, dl = delta_s[m % NST][32 * is + li];
+      // The wave's instructions are ordered by hand so that its matrix instructions always have vector work of the same
+      // wave beside them:
+      //   1. S^T = K Q^T            between its matrix instructions: the two Philox calls of the tile (indices only);
+      //   2. dD^T = V dO^T          between them: P = exp2(..), the keep decisions, D = P M / (1-p) (need S only);
+      //   3. dS = P (dD M / (1-p) - delta), rounding to bf16.
+      Philox4 rnd[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+      if (DROP) {
+        const uint64_t rowG = headG + (uint64_t)i * (uint64_t)(P.s >> 3);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) rnd[c] = philox_start(rowG + (uint64_t)((jw0 + 16 * c + 8 * hh) >> 3), 0u);
+      }
+      constexpr int kAhead = 3;
+      bf16x8_t qa[kAhead], da[kAhead];
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) qa[a] = ld_frag(qrow + 16 * a);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        st = mfma32(kf[kc], qa[kc % kAhead], st);
+        if (kc + kAhead < KC) qa[kc % kAhead] = ld_frag(qrow + 16 * (kc + kAhead));
+        if (kc >= KC - kAhead) da[kc - (KC - kAhead)] = ld_frag(drow + 16 * (kc - (KC - kAhead)));
+        if (DROP) {
+#pragma unroll
+          for (int u = (20 * kc) / KC; u < (20 * (kc + 1)) / KC; ++u) philox_round(rnd[u & 1], P.key0, P.key1, u >> 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (P.causal && m == kb) {  // the diagonal tile: keys j > i get probability exp2(-inf) = 0
+        asm volatile("" ::: "memory");  // keep this a branch: all other tiles skip it
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
+      }
+      float pe[16], km[16], dvv[16];
+#pragma unroll
+      for (int kc = 0; kc < KC; ++kc) {
+        dd = mfma32(vf[kc], da[kc % kAhead], dd);
+        if (kc + kAhead < KC) da[kc % kAhead] = ld_frag(drow + 16 * (kc + kAhead));
+        // 16 exponent arguments, the two blocks of eight keep decisions, 16 exponentials, 16 products, dealt out in this order
+        // over the windows: a window then holds one kind of operation on different elements (dependent instructions would
+        // run at their latency)
+        constexpr int NOPS = 50;  // 16 + 2 + 16 + 16
+#pragma unroll
+        for (int o = (NOPS * kc) / KC; o < (NOPS * (kc + 1)) / KC; ++o) {
+          if (o < 16) pe[o] = fmaf(st[o], sc2, -lse2);
+          else if (o < 18) {
+            const int c = o - 16;
+            if (DROP) {
+              float k8[8];
+              keep_scale8(rnd[c], P.thresh, P.keep_scale, k8);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) km[8 * c + e] = k8[e];
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) km[8 * c + e] = P.keep_scale;
+            }
+          } else if (o < 34) pe[o - 18] = __builtin_amdgcn_exp2f(pe[o - 18]);
+          else dvv[o - 34] = pe[o - 34] * km[o - 34];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      bf16x8_t df[2], dsf[2];
+      df[0] = pack8(dvv);
+      df[1] = pack8(dvv + 8);
+      {
+        float ds[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ds[e] = pe[e] * (dd[e] * km[e] - dl);
+        dsf[0] = pack8(ds);
+        dsf[1] = pack8(ds + 8);
+      }
+      if constexpr (WDS) {
+        ds_store2(ds_tile, lane, dsf[0], dsf[1]);
+        ds_tile += ds_step;
+        if (P.causal) ds_step += kDsTileElems;
+      }
+      bf16x8_t* x = reinterpret_cast<bf16x8_t*>(&xb[m & 1][w][0][0]) + lane;
+      x[0] = df[0];
+      x[64] = df[1];
+      x[128] = dsf[0];
+      x[192] = dsf[1];
+    }
+    // the barriers of the consumers' epilogue
+    __syncthreads();
+    __syncthreads();
+    __syncthreads();
+  } else {
+    // ---- consumer ----
+    DmaMap<D> map;
+    map.init(w, lane, gstride, false);
+    auto fetch = [&](int it, int round) __attribute__((always_inline)) {  // rounds 0 .. 2 PER - 1 of tile `it`
+      constexpr int PER = DmaMap<D>::PER;
+      uint16_t* dst = smem + (it % NST) * 2 * TILE;
+      if (round < PER) dma_one<D>(map, qg + (int64_t)(it * BI) * gstride, dst, w, round);
+      else dma_one<D>(map, dog + (int64_t)(it * BI) * gstride, dst + TILE, w, round - PER);
+    };
+    auto fetch_stats = [&](int it) __attribute__((always_inline)) {  // one float per row, straight into LDS
+      dma4(lse + (size_t)bn * P.s + it * BI + lane, lds_addr(lse_s[it % NST]));
+      dma4(delta + (size_t)bn * P.s + it * BI + lane, lds_addr(delta_s[it % NST]));
+    };
+    constexpr int NR = 2 * DmaMap<D>::PER;
+#pragma unroll
+    for (int r = 0; r < NR; ++r) fetch(it0, r);
+    if (w == 0) fetch_stats(it0);
+    // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
+    bf16x8_t ident[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      union { uint16_t h[8]; bf16x8_t v; } u;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) u.h[e] = (li == 16 * c + 8 * hh + e) ? (uint16_t)0x3F80 : (uint16_t)0;
+      ident[c] = u.v;
+    }
+    float16_t dkacc[DT], dvacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
+
+    for (int m = it0; m <= nit; ++m) {
+      dma_wait();       // this wave's share of tile m has landed
+      __syncthreads();  // ... and everybody's; the producers have written exchange buffer (m - 1) & 1 and read tile m - 1
+      const bool more = m + 1 < nit;
+      if (more && w == 0) fetch_stats(m + 1);
+      if (m == it0) {  // nothing to consume yet
+        if (more) {
+#pragma unroll
+          for (int r = 0; r < NR; ++r) fetch(m + 1, r);
+        }
+        continue;
+      }
+      const int t = m - 1;
+      const uint16_t* Qs = smem + (t % NST) * 2 * TILE;
+      const uint16_t* dOs = Qs + TILE;
+      const bf16x8_t* x = reinterpret_cast<const bf16x8_t*>(&xb[t & 1][w][0][0]) + lane;
+      const bf16x8_t df0 = x[0], df1 = x[64], ds0 = x[128], ds1 = x[192];
+      // one-key-per-lane copies: T[i][key] = sum_k tile[i][k] I[k][key]
+      float16_t tD, tS;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { tD[e] = 0.f; tS[e] = 0.f; }
+      tD = mfma32(df0, ident[0], tD);
+      tS = mfma32(ds0, ident[0], tS);
+      tD = mfma32(df1, ident[1], tD);
+      tS = mfma32(ds1, ident[1], tS);
+      if (more) { fetch(m + 1, 0); fetch(m + 1, 1); }
+      // acc[4g + r] <-> row 8g + 4hh + r: operand X takes g in {2X, 2X+1}, i.e. rows 16X + 8*(e>>2) + 4hh + (e&3)
+      constexpr int kAhead = 2, NP = 2 * DT;
+      bf16x8_t oa[kAhead], qa[kAhead];
+      auto tr = [&](const uint16_t* tile, int p) __attribute__((always_inline)) {
+        return ld_frag_tr_perm(tile, KP, 32 * is + 16 * (p / DT), 32 * (p % DT), lane);
+      };
+#pragma unroll
+      for (int a = 0; a < kAhead; ++a) oa[a] = tr(dOs, a), qa[a] = tr(Qs, a);
+      bf16x8_t dT[2], sT[2];
+#pragma unroll
+      for (int X = 0; X < 2; ++X) {
+        float td[8], ts[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { td[e] = tD[8 * X + e]; ts[e] = tS[8 * X + e]; }
+        dT[X] = pack8(td);
+        sT[X] = pack8(ts);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+        dvacc[p % DT] = mfma32(oa[p % kAhead], dT[p / DT], dvacc[p % DT]);
+        dkacc[p % DT] = mfma32(qa[p % kAhead], sT[p / DT], dkacc[p % DT]);
+        if (p + kAhead < NP) oa[p % kAhead] = tr(dOs, p + kAhead), qa[p % kAhead] = tr(Qs, p + kAhead);
+        // the rest of the next tile's loads, dealt out between the products
+        if (more && 2 + p < NR) fetch(m + 1, 2 + p);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      static_assert(NR - 2 <= NP, "more load rounds than pairs of products");
+    }
+    // ---- sum the two row halves, scale, store ----
+    __syncthreads();
+    // each wave of a pair gives one accumulator set away and finishes the other: the upper half completes dV, the lower dK
+    float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
+    if (is == 1) acc_put<DT>(mg, dkacc, lane);
+    else acc_put<DT>(mg + 16 * DT * 64, dvacc, lane);
+    __syncthreads();
+    if (is == 0) {
+      acc_combine<DT>(mg, dkacc, 1.f, 1.f, lane);
+      acc_to_lds_rows<DT>(smem + 4 * TILE, KP, 32 * kgp + li, dkacc, P.scale, hh);
+    } else {
+      acc_combine<DT>(mg + 16 * DT * 64, dvacc, 1.f, 1.f, lane);
+      acc_to_lds_rows<DT>(smem + 5 * TILE, KP, 32 * kgp + li, dvacc, 1.0f, hh);
+    }
+    __syncthreads();
+  }
+  // all eight waves: the producers' threads copy dK out, the consumers' dV
+  if (tid < 256) lds_rows_to_global<D>(smem + 4 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
+  else lds_rows_to_global<D>(smem + 5 * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid - 256);
+}
+
+}  // namespace sar

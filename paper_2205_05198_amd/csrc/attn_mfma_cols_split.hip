@@ -1,0 +1,36 @@
+// bf16 attention core, backward column pass (dK, dV) in its producer / consumer form (two waves per SIMD, each within
+// 256 vector registers; compiled WITH -amdgpu-mfma-vgpr-form): head dimensions 128 and 160, s % 64 == 0.
+#define SAR_COLS_ACC "v"
+#include "attn_mfma_cols_split.h"
+
+namespace sar {
+
+template <int D>
+static hipError_t bwd_dkdv_split_d(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO, const float* delta,
+                                   void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
+  const int N = P.b * P.A, nb = P.s / 64;
+  auto go = [&](auto kern) {
+    hipLaunchKernelGGL(kern, dim3((unsigned)(nb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, lse,
+                       (const uint16_t*)dO, delta, (uint16_t*)dk, (uint16_t*)dv, ds_ws);
+  };
+  if (ds_ws) {
+    if (P.thresh != 0) go(attn_bwd_dkdv_split_kernel<D, true, true>);
+    else go(attn_bwd_dkdv_split_kernel<D, false, true>);
+  } else {
+    if (P.thresh != 0) go(attn_bwd_dkdv_split_kernel<D, true, false>);
+    else go(attn_bwd_dkdv_split_kernel<D, false, false>);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bwd_dkdv_mfma_split(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
+                                           const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
+  if (P.s % 64 != 0) return hipErrorInvalidValue;
+  switch (P.d) {
+    case 128: return bwd_dkdv_split_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    case 160: return bwd_dkdv_split_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace sar

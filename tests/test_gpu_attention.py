@@ -181,7 +181,7 @@ def test_random_shapes_and_kernel_variants():
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = [rng.choice([-1, 0, 1]) for _ in range(4)]
+        env = [rng.choice([-1, 0, 1]) for _ in range(3)] + [rng.choice([-1, 0, 1, 2])]
         if s < 128:
             env[0] = -1
         sar.sar_test_force_variants(*env)
@@ -193,13 +193,13 @@ def test_random_shapes_and_kernel_variants():
         _check_bf16_heads(f"sweep{case}", sh, q, k, v, do, got, range(b * A))
 
 
-@pytest.mark.parametrize("pipe", [0, 1])
+@pytest.mark.parametrize("pipe", [0, 1, 2])
 @pytest.mark.parametrize("two_pass", [False, True])
 @pytest.mark.parametrize("d,s,b,A,p,causal", [(160, 320, 1, 2, 0.1, 1), (128, 256, 2, 1, 0.25, 1), (160, 192, 1, 2, 0.1, 0), (128, 64, 1, 2, 0.0, 1), (160, 128, 1, 1, 0.0, 0)])
 def test_column_pass_pipelined_and_plain(d, s, b, A, p, causal, two_pass, pipe):
-    """The column pass in its software-pipelined form (three query-tile stages, K operands in registers) and in its plain
-    form, both forced, on sequences of one to five full tiles: with and without the mask, with and without dropout, in
-    both forms of the backward."""
+    """The column pass in its plain form (0), its software-pipelined form (1: three query-tile stages, K operands in
+    registers) and its producer / consumer form (2: two waves per SIMD), each forced, on sequences of one to five full
+    tiles: with and without the mask, with and without dropout, in both forms of the backward."""
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(-1, -1, -1, pipe)

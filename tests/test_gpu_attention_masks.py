@@ -115,9 +115,9 @@ def test_fused_kernel_masks_kernel_variants():
         # the column pass, pipelined and plain, at a length of full tiles (s % 64 == 0), both head dimensions it exists for
         for d in (128, 160):
             sh2 = oracle.AttnShape(s=320, b=1, a=4, h=4 * d, t=2, rank=1, p=0.25, seed=99, offset=(1 << 32) - 4000)
-            for pipe in (0, 1):
+            for pipe in (0, 1, 2):
                 sar.sar_test_force_variants(-1, -1, -1, pipe)
-                print(f"masks column pass pipelined={pipe} d={d}", flush=True)
+                print(f"masks column pass form={pipe} d={d}", flush=True)
                 for two_pass in (False, True):
                     _compare(sh2, "dv", two_pass)
                     _compare(sh2, "dq", two_pass)
