@@ -18,6 +18,9 @@
 // accumulation registers.
 #pragma once
 #include "attn_mfma_cols_kernel.h"
+#ifndef SAR_EXP
+#define SAR_EXP 0
+#endif
 
 namespace sar {
 
@@ -46,22 +49,36 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   const int it0 = P.causal ? kb : 0;
   const uint16_t* qg = q + base;
   const uint16_t* dog = dO + base;
+#if SAR_EXP == 46
+  const uint64_t R_in = __builtin_amdgcn_s_memrealtime();
+  uint64_t R_first = 0, R_loop = 0;
+#endif
 
   if (producer) {
-    // ---- K and V operands of this wave's 32 keys, for the whole kernel: lane li holds key jw0 + perm_row(li) ----
+    // ---- K and V operands of this wave's 32 keys, for the whole kernel: lane li holds key jw0 + perm_row(li).  They come
+    // through LDS (coalesced direct loads into the stage that tile it0 + 1 will take; rows swapped inside groups of 32):
+    // fetched straight into registers, every lane reads 20 separate 16-byte pieces of its own row ----
     bf16x8_t kf[KC], vf[KC];
     {
-      const int64_t row = base + (int64_t)(jw0 + perm_row(li)) * P.stride_s + 8 * hh;
+      DmaMap<D> kvmap;
+      kvmap.init(w, lane, gstride, true);
+      uint16_t* Kst = smem + ((it0 + 1) % NST) * 2 * TILE;
+      dma_tile<D>(kvmap, k + base + (int64_t)(kb * BN) * gstride, Kst, w);
+      dma_tile<D>(kvmap, v + base + (int64_t)(kb * BN) * gstride, Kst + TILE, w);
+      dma_wait();
+      __syncthreads();  // the K and V blocks are staged
+      const uint16_t* kw = Kst + (32 * kgp + li) * KP + 8 * hh;
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
-        kf[kc] = ld_frag(k + row + 16 * kc);
-        vf[kc] = ld_frag(v + row + 16 * kc);
+        kf[kc] = ld_frag(kw + 16 * kc);
+        vf[kc] = ld_frag(kw + TILE + 16 * kc);
       }
 #pragma unroll
-      for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(kf[kc]), "+v"(vf[kc]));
+      for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(kf[kc]), "+v"(vf[kc]));  // read before the barrier that frees the stage
     }
     const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
     const float sc2 = P.scale * kLog2e;
+    const float log2_keep_scale = __builtin_amdgcn_logf(P.keep_scale), inv_keep_scale = 1.0f / P.keep_scale;  // v_log_f32 is log2
     uint16_t* ds_tile = nullptr;  // uniform: the wave's 2 KB of the dS tile (it, kb)
     int64_t ds_step = 0;
     if constexpr (WDS) {
@@ -70,6 +87,9 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     }
     for (int m = it0; m <= nit; ++m) {
       __syncthreads();  // tile m is in its stage; the consumer has read exchange buffer m & 1 (tile m - 2)
+#if SAR_EXP == 46
+      if (m == it0) R_first = __builtin_amdgcn_s_memrealtime();
+#endif
       if (m == nit) break;
       const uint16_t* Qs = smem + (m % NST) * 2 * TILE;
       const uint16_t* qrow = Qs + (32 * is + li) * KP + 8 * hh;
@@ -78,7 +98,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
 #pragma unroll
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
       const int i = m * BI + 32 * is + li;
-      const float lse2 = lse_s[m % NST][32 * is + li] * kLog2e, dl = delta_s[m % NST][32 * is + li];
+      // lse2q: the row's LSE in log2 units minus log2 of 1/(1-p); dlq: delta (1-p)
+      const float lse2q = lse_s[m % NST][32 * is + li] * kLog2e - log2_keep_scale, dlq = delta_s[m % NST][32 * is + li] * inv_keep_scale;
       // The wave's instructions are ordered by hand so that its matrix instructions always have vector work of the same
       // wave beside them:
       //   1. S^T = K Q^T            between its matrix instructions: the two Philox calls of the tile (indices only);
@@ -112,31 +133,30 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         for (int e = 0; e < 16; ++e)
           if (jw0 + 16 * (e >> 3) + 8 * hh + (e & 7) > i) st[e] = -INFINITY;
       }
-      float pe[16], km[16], dvv[16];
+      // Q = P / (1-p) comes straight out of the exponential (log2 of the scale folded into the row's LSE term), so that
+      // D = M Q is one select and dS = P (dD M / (1-p) - delta) = D dD - Q delta (1-p) two more operations per element.
+      float pq[16], dvv[16];
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
         dd = mfma32(vf[kc], da[kc % kAhead], dd);
         if (kc + kAhead < KC) da[kc % kAhead] = ld_frag(drow + 16 * (kc + kAhead));
-        // 16 exponent arguments, the two blocks of eight keep decisions, 16 exponentials, 16 products, dealt out in this order
+        // 16 exponent arguments, 16 exponentials, the two blocks of eight keep selects, 16 products, dealt out in this order
         // over the windows: a window then holds one kind of operation on different elements (dependent instructions would
         // run at their latency)
-        constexpr int NOPS = 50;  // 16 + 2 + 16 + 16
+        constexpr int NOPS = 50;  // 16 + 16 + 2 + 16
 #pragma unroll
         for (int o = (NOPS * kc) / KC; o < (NOPS * (kc + 1)) / KC; ++o) {
-          if (o < 16) pe[o] = fmaf(st[o], sc2, -lse2);
-          else if (o < 18) {
-            const int c = o - 16;
+          if (o < 16) pq[o] = fmaf(st[o], sc2, -lse2q);
+          else if (o < 32) pq[o - 16] = __builtin_amdgcn_exp2f(pq[o - 16]);
+          else if (o < 34) {
+            const int c = o - 32;
             if (DROP) {
-              float k8[8];
-              keep_scale8(rnd[c], P.thresh, P.keep_scale, k8);
-#pragma unroll
-              for (int e = 0; e < 8; ++e) km[8 * c + e] = k8[e];
+              keep_select8(rnd[c], P.thresh, reinterpret_cast<const float(&)[8]>(pq[8 * c]), reinterpret_cast<float(&)[8]>(dvv[8 * c]));
             } else {
 #pragma unroll
-              for (int e = 0; e < 8; ++e) km[8 * c + e] = P.keep_scale;
+              for (int e = 0; e < 8; ++e) dvv[8 * c + e] = pq[8 * c + e];
             }
-          } else if (o < 34) pe[o - 18] = __builtin_amdgcn_exp2f(pe[o - 18]);
-          else dvv[o - 34] = pe[o - 34] * km[o - 34];
+          } else pq[o - 34] *= dlq;  // Q delta (1-p)
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -146,7 +166,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       {
         float ds[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) ds[e] = pe[e] * (dd[e] * km[e] - dl);
+        for (int e = 0; e < 16; ++e) ds[e] = fmaf(dvv[e], dd[e], -pq[e]);
         dsf[0] = pack8(ds);
         dsf[1] = pack8(ds + 8);
       }
@@ -161,6 +181,9 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       x[128] = dsf[0];
       x[192] = dsf[1];
     }
+#if SAR_EXP == 46
+    R_loop = __builtin_amdgcn_s_memrealtime();
+#endif
     // the barriers of the consumers' epilogue
     __syncthreads();
     __syncthreads();
@@ -183,6 +206,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
 #pragma unroll
     for (int r = 0; r < NR; ++r) fetch(it0, r);
     if (w == 0) fetch_stats(it0);
+    __syncthreads();  // the producers have staged K and V (they read them before the first barrier of the loop)
     // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
     bf16x8_t ident[2];
 #pragma unroll
@@ -272,6 +296,12 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   // all eight waves: the producers' threads copy dK out, the consumers' dV
   if (tid < 256) lds_rows_to_global<D>(smem + 4 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
   else lds_rows_to_global<D>(smem + 5 * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid - 256);
+#if SAR_EXP == 46
+  if (tid == 0) {
+    uint64_t* dbg = reinterpret_cast<uint64_t*>(ds_ws + (int64_t)N * ds_tiles_per_head(P) * kDsTileElems) + (size_t)blockIdx.x * 8;
+    dbg[0] = R_in; dbg[1] = R_first; dbg[2] = R_loop; dbg[3] = __builtin_amdgcn_s_memrealtime(); dbg[4] = nit - it0;
+  }
+#endif
 }
 
 }  // namespace sar
