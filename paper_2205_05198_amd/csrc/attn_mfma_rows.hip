@@ -25,6 +25,7 @@
 #include "attn_mfma_common.h"
 #include <atomic>
 #include <type_traits>
+#include "attn_mfma_fwd_split.h"
 
 namespace sar {
 
@@ -585,6 +586,18 @@ static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const
     // loader waves: measured -10 % at d = 160 (530B shard), -9 % at d = 128 (175B), -8 % at d = 64, +15 % at d = 96 (22B
     // shard: three 4-wave workgroups share a CU there and fill each other's stalls).
     const int lw = g_force_fwdlw.load();
+    // producer / consumer pairs: measured against the tile-fetching waves -16 % at d = 64 (22B shard), +2 % at d = 160,
+    // +12 % at d = 128: where the head dimension is small the matrix and LDS work that moves to the second wave is a larger
+    // share of a step, at d >= 128 the vector work that stays is the step
+    if (lw == 2 || (lw < 0 && D == 64)) {
+      if (P.thresh != 0)
+        hipLaunchKernelGGL((attn_fwd_split_kernel<D, true>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (uint16_t*)o, lse);
+      else
+        hipLaunchKernelGGL((attn_fwd_split_kernel<D, false>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (uint16_t*)o, lse);
+      return hipGetLastError();
+    }
     const bool use_lw = (lw == 0 || lw == 1) ? lw == 1 : D != 96;
     if (use_lw) {
       if (P.thresh != 0)

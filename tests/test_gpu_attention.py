@@ -138,11 +138,12 @@ def test_forward_with_128_row_workgroups(d, s, causal):
     _check_bf16_heads("fwd128", sh, q, k, v, do, got, range(2))
 
 
-@pytest.mark.parametrize("lw", [0, 1])
-@pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (96, 200, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1)])
+@pytest.mark.parametrize("lw", [0, 1, 2])
+@pytest.mark.parametrize("d,s,causal", [(64, 328, 1), (96, 200, 1), (160, 328, 1), (160, 200, 0), (128, 136, 1), (160, 40, 1)])
 def test_forward_with_and_without_loader_waves(d, s, causal, lw):
-    """The 64-row forward kernel and the dQ pass with (8 waves) and without (4 waves) their tile-fetching waves, both forced
-    whatever the library would pick for the head dimension, on ragged shapes (the last tile is fetched with clamped rows)."""
+    """The 64-row forward kernel and the dQ pass with (1: 8 waves) and without (0: 4 waves) their tile-fetching waves, and
+    the forward as producer / consumer wave pairs (2), each forced whatever the library would pick for the head dimension,
+    on ragged shapes (the last tile is fetched with clamped rows; s = 40: a single tile)."""
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(0, lw, lw)
@@ -181,7 +182,7 @@ def test_random_shapes_and_kernel_variants():
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = [rng.choice([-1, 0, 1]) for _ in range(3)] + [rng.choice([-1, 0, 1, 2])]
+        env = [rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2]), rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2])]
         if s < 128:
             env[0] = -1
         sar.sar_test_force_variants(*env)

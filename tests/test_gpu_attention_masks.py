@@ -107,7 +107,7 @@ def test_fused_kernel_masks_kernel_variants():
     """The forward's other variants (128-row workgroups; without loader waves) and both forms of the column pass draw the same mask."""
     sh = oracle.AttnShape(s=328, b=1, a=4, h=4 * 160, t=2, rank=1, p=0.25, seed=99, offset=12345)
     try:
-        for variant in ((1, -1, -1, -1), (0, 0, 0, -1), (0, 1, 1, -1)):
+        for variant in ((1, -1, -1, -1), (0, 0, 0, -1), (0, 1, 1, -1), (0, 2, -1, -1)):
             sar.sar_test_force_variants(*variant)
             print(f"masks variants={variant}", flush=True)
             _compare(sh, "fwd")
