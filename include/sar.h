@@ -268,8 +268,8 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
  *   fwd_loader_waves  forward (64-row workgroups) with four extra waves that only fetch K / V tiles (1), or as producer /
  *                     consumer wave pairs (2: one wave computes scores and softmax, the other accumulates P V and fetches)
  *   dq_loader_waves   the same for the row pass of the recompute-twice backward
- *   dkdv_pipelined    form of the column pass, for head dimension 128 and 160 and s % 64 == 0: 0 plain; 1 software-pipelined
- *                     (score tiles of the next query tile computed beside this tile's vector arithmetic); 2 producer /
+ *   dkdv_pipelined    form of the column pass where s % 64 == 0: 0 plain; 1 software-pipelined (head dimension 128 and 160
+ *                     only: score tiles of the next query tile computed beside this tile's vector arithmetic); 2 producer /
  *                     consumer (two waves per SIMD: one computes scores, softmax, mask and dS, the other accumulates dK, dV)
  * Process-wide; not meant to be changed while another thread launches.
  */

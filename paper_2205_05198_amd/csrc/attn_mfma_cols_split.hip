@@ -1,5 +1,5 @@
 // bf16 attention core, backward column pass (dK, dV) in its producer / consumer form (two waves per SIMD, each within
-// 256 vector registers; compiled WITH -amdgpu-mfma-vgpr-form): head dimensions 128 and 160, s % 64 == 0.
+// 256 vector registers; compiled WITH -amdgpu-mfma-vgpr-form): every head dimension of the matrix-core path, s % 64 == 0.
 #define SAR_COLS_ACC "v"
 #include "attn_mfma_cols_split.h"
 
@@ -27,6 +27,8 @@ hipError_t launch_attn_bwd_dkdv_mfma_split(const AttnParams& P, const void* q, c
                                            const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
   if (P.s % 64 != 0) return hipErrorInvalidValue;
   switch (P.d) {
+    case 64: return bwd_dkdv_split_d<64>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+    case 96: return bwd_dkdv_split_d<96>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     case 128: return bwd_dkdv_split_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     case 160: return bwd_dkdv_split_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     default: return hipErrorInvalidValue;

@@ -196,7 +196,8 @@ def test_random_shapes_and_kernel_variants():
 
 @pytest.mark.parametrize("pipe", [0, 1, 2])
 @pytest.mark.parametrize("two_pass", [False, True])
-@pytest.mark.parametrize("d,s,b,A,p,causal", [(160, 320, 1, 2, 0.1, 1), (128, 256, 2, 1, 0.25, 1), (160, 192, 1, 2, 0.1, 0), (128, 64, 1, 2, 0.0, 1), (160, 128, 1, 1, 0.0, 0)])
+@pytest.mark.parametrize("d,s,b,A,p,causal", [(160, 320, 1, 2, 0.1, 1), (128, 256, 2, 1, 0.25, 1), (160, 192, 1, 2, 0.1, 0), (128, 64, 1, 2, 0.0, 1), (160, 128, 1, 1, 0.0, 0),
+                                              (64, 320, 2, 1, 0.1, 1), (96, 192, 1, 2, 0.25, 0), (64, 64, 1, 1, 0.0, 1)])
 def test_column_pass_pipelined_and_plain(d, s, b, A, p, causal, two_pass, pipe):
     """The column pass in its plain form (0), its software-pipelined form (1: three query-tile stages, K operands in
     registers) and its producer / consumer form (2: two waves per SIMD), each forced, on sequences of one to five full

@@ -112,8 +112,9 @@ def test_fused_kernel_masks_kernel_variants():
             print(f"masks variants={variant}", flush=True)
             _compare(sh, "fwd")
             _compare(sh, "dq", two_pass=True)
-        # the column pass, pipelined and plain, at a length of full tiles (s % 64 == 0), both head dimensions it exists for
-        for d in (128, 160):
+        # the column pass in its three forms at a length of full tiles (s % 64 == 0), every head dimension (a form that does not
+        # exist at a head dimension falls back to the plain one)
+        for d in (64, 96, 128, 160):
             sh2 = oracle.AttnShape(s=320, b=1, a=4, h=4 * d, t=2, rank=1, p=0.25, seed=99, offset=(1 << 32) - 4000)
             for pipe in (0, 1, 2):
                 sar.sar_test_force_variants(-1, -1, -1, pipe)
