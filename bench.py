@@ -31,6 +31,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="530B")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--spinup-ms", type=float, default=300.0,
+                    help="untimed steps run for this long before the warm-up: from idle the GPU's clocks need some hundred ms of load to settle "
+                         "(the first 10 ms after idle run about 8 %% slower), which 5 warm-up steps (1 ms) do not provide")
+    ap.add_argument("--event-sample", type=int, default=4, help="the dominant kernel is bracketed by two HIP events on every n-th step of the timed region")
     ap.add_argument("--graph", action="store_true",
                     help="replay one HIP graph per step instead of launching the step's kernels from the host (measured slower here: a replay costs "
                          "about 10 us of launch latency, while host launches run ahead of the GPU and leave no gaps)")
@@ -150,14 +154,22 @@ def main():
                     c()
                     if i == DOM:
                         e1.record()
+        t_spin = time.perf_counter()
+        while (time.perf_counter() - t_spin) * 1e3 < args.spinup_ms:
+            for _ in range(20):
+                run_step()
+            torch.cuda.synchronize()
         for _ in range(args.warmup):
             run_step()
         torch.cuda.synchronize()
         # Timed region: exactly `steps` steps.  An event record costs stream time, so only the dominant kernel is bracketed,
         # on every 4th step.
-        SAMPLE = 4
+        SAMPLE = max(1, args.event_sample)
         nsamp = (args.steps + SAMPLE - 1) // SAMPLE
         dom_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(nsamp)]
+        for a, b_ in dom_ev:  # torch creates the underlying HIP event at the first record: not inside the timed region
+            a.record()
+            b_.record()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -304,8 +316,9 @@ def main():
         "config": {"workload": f"{args.workload}-class per-GPU shard: attention core b={b} s={s} heads={A} head_dim={d} {'causal' if w.causal else 'no mask'} p={w.p}; "
                                f"LayerNorm fwd/bwd + bias-dropout-add on {rows}x{h} bf16", "t": w.t,
                    "backward": "region recomputed once (dS tiles in the workspace)" if once else "region recomputed twice (row pass + column pass)",
-                   "launch": ("one HIP graph replay per step (every 4th step: two graphs around the event-bracketed dominant kernel)" if use_graph
-                              else "host launches, asynchronous (every 4th step: two event records around the dominant kernel)")},
+                   "launch": (f"one HIP graph replay per step (every {SAMPLE}th step: two graphs around the event-bracketed dominant kernel)" if use_graph
+                              else f"host launches, asynchronous (every {SAMPLE}th step: two event records around the dominant kernel)"),
+                   "spinup_ms": args.spinup_ms},
         "pct_mfma_peak": 100.0 * value / PEAK_BF16_MFMA_TFLOPS,
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic,
