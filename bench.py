@@ -442,6 +442,22 @@ def side_measurements(args, sar, torch, np, w, rdesc, rows, h, esz, bytes_alg, t
                                "note": "register-resident loop of 32x32x16 bf16 matrix instructions, 8 waves per CU; copy of 1 GiB (read + write counted); medians of 5"}
     res["rows_kernels_frac_attainable_hbm"] = {n: res["rows_kernels_gbs_cold"][n] / copy_gbs for n in kern}
 
+    # what an instruction costs the wave that issues it (one wave per SIMD; the two-wave probes give both waves' figures)
+    with torch.cuda.stream(side):
+        nwg, iters = 64, 200
+        cyc = torch.zeros(nwg * 8, dtype=torch.int64, device="cuda")
+        issue = {}
+        for pi, pname in enumerate(sar.sar_bench_issue_names()):
+            sar.sar_bench_issue(pi, iters, cyc, sink)       # once to warm the instruction cache
+            ia, ib = sar.sar_bench_issue(pi, iters, cyc, sink)
+            torch.cuda.synchronize()
+            c = cyc.view(nwg, 8).double().cpu().numpy()
+            val = [round(float(c[:, :4].mean()) / (iters * ia), 2)]
+            if ib:
+                val.append(round(float(c[:, 4:].mean()) / (iters * ib), 2))
+            issue[pname] = val if len(val) > 1 else val[0]
+    res["issue_cycles_per_instruction"] = issue
+
     # the kernels next to the hot path (not part of a step), hot-cache figures
     x, resid, dy, bias, gamma, beta, y, dx, out, mean, rstd = (t[n] for n in ("x", "resid", "dy", "bias", "gamma", "beta", "y", "dx", "out", "mean", "rstd"))
     dbias = torch.empty(h, dtype=torch.float32, device="cuda")

@@ -286,6 +286,16 @@ void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_load
  */
 sar_status sar_bench_mfma(int iters, float* sink, double* flops_out, void* stream);
 sar_status sar_bench_copy(const void* src, void* dst, size_t bytes, void* stream);
+/*
+ *   sar_bench_issue  enqueues probe number `probe` (0 .. until sar_bench_issue_name returns NULL) on `workgroups` workgroups:
+ *                    waves 0..3 of a workgroup (one per SIMD) run `iters` iterations of one unrolled instruction sequence, and in
+ *                    the two-wave probes waves 4..7 run a second one beside them.  cycles: device, workgroups x 8 values, written
+ *                    at [workgroup * 8 + wave] with the wave's s_memtime cycles for all its iterations; insts_a / insts_b
+ *                    (host, out): instructions per iteration of the two sequences (0 if there is no second).  sink: device, one
+ *                    float, never written.  Cycles per instruction = cycles / (iters x insts).
+ */
+const char* sar_bench_issue_name(int probe);
+sar_status sar_bench_issue(int probe, int iters, unsigned long long* cycles, int workgroups, float* sink, int* insts_a, int* insts_b, void* stream);
 
 /* Thread-local text describing the last non-OK status returned on this thread ("" if none). */
 const char* sar_last_error(void);

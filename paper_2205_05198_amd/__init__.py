@@ -10,5 +10,5 @@ from .binding import (  # noqa: F401
     attn_core_fwd, attn_core_fwd_stored, attn_core_philox_count, attn_core_saved_bytes,
     attn_core_small_buffer_bytes, bias_dropout_add, bias_dropout_add_bwd, bias_dropout_add_bwd_workspace,
     bias_dropout_add_ln_fwd, bias_gelu_bwd, bias_gelu_bwd_workspace, bias_gelu_fwd, build_library, library_path, ln_bwd, ln_bwd_workspace,
-    ln_fwd, load_library, sar_bench_copy, sar_bench_mfma, sar_last_error,
+    ln_fwd, load_library, sar_bench_copy, sar_bench_issue, sar_bench_issue_names, sar_bench_mfma, sar_last_error,
 )

@@ -142,6 +142,8 @@ def load_library():
         "bias_gelu_bwd": (ctypes.c_int, [rd, vp, vp, vp, vp, vp, vp, sz, vp]),
         "sar_bench_mfma": (ctypes.c_int, [ctypes.c_int, vp, ctypes.POINTER(ctypes.c_double), vp]),
         "sar_bench_copy": (ctypes.c_int, [vp, vp, sz, vp]),
+        "sar_bench_issue_name": (ctypes.c_char_p, [ctypes.c_int]),
+        "sar_bench_issue": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, vp, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int), vp]),
         "sar_last_error": (ctypes.c_char_p, []),
     }
     for name, (res, args) in protos.items():
@@ -158,7 +160,7 @@ EXPORTS = ["attn_core_fwd", "attn_core_bwd_workspace", "attn_core_bwd_workspace_
            "attn_core_bwd_stored", "attn_core_saved_bytes", "attn_core_small_buffer_bytes", "attn_core_philox_count",
            "ln_fwd", "ln_bwd_workspace", "ln_bwd", "bias_dropout_add", "bias_dropout_add_ln_fwd",
            "bias_dropout_add_bwd_workspace", "bias_dropout_add_bwd", "bias_gelu_fwd", "bias_gelu_bwd_workspace", "bias_gelu_bwd",
-           "sar_bench_mfma", "sar_bench_copy", "sar_last_error"]
+           "sar_bench_mfma", "sar_bench_copy", "sar_bench_issue_name", "sar_bench_issue", "sar_last_error"]
 
 
 def _ptr(t):
@@ -186,6 +188,26 @@ def sar_bench_mfma(iters: int, sink) -> float:
     if st != 0:
         raise SarError(st, "sar_bench_mfma")
     return fl.value
+
+
+def sar_bench_issue_names():
+    """Names of the issue-cost probes, in probe order."""
+    lib, out, i = load_library(), [], 0
+    while True:
+        n = lib.sar_bench_issue_name(i)
+        if n is None:
+            return out
+        out.append(n.decode())
+        i += 1
+
+
+def sar_bench_issue(probe: int, iters: int, cycles, sink):
+    """Enqueues one probe; cycles: int64 device tensor of workgroups * 8 elements.  Returns (insts_a, insts_b)."""
+    ia, ib = ctypes.c_int(0), ctypes.c_int(0)
+    st = load_library().sar_bench_issue(probe, iters, _ptr(cycles), cycles.numel() // 8, _ptr(sink), ctypes.byref(ia), ctypes.byref(ib), _stream())
+    if st != 0:
+        raise SarError(st, "sar_bench_issue")
+    return ia.value, ib.value
 
 
 def sar_bench_copy(src, dst):
