@@ -7,6 +7,7 @@ in s), the backward's scratch and form, and measured forward / backward time.
 Prints a markdown table.  Needs a GPU; inputs are seeded synthetic draws as in bench.py.
 """
 import argparse
+import time
 
 import numpy as np
 
@@ -37,9 +38,12 @@ def main():
         ws = torch.empty(nws, dtype=torch.uint8, device="cuda")
 
         def timed(fn):
-            for _ in range(2):
-                fn()
-            torch.cuda.synchronize()
+            # untimed launches first, for 0.3 s: from idle the GPU's clocks take some hundred ms of load to settle
+            t_spin = time.perf_counter()
+            while time.perf_counter() - t_spin < 0.3:
+                for _ in range(2):
+                    fn()
+                torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(args.iters):
