@@ -84,8 +84,12 @@ __global__ __launch_bounds__(128 * NRG + (LW ? 256 : 0)) void attn_fwd_mfma_kern
       fetch(k + base, Kst, 0);
       fetch(v + base, Vst, 0);
       if (nt > 1) fetch(k + base, Kst, 1);
-      dma_wait();
-      __syncthreads();  // tiles K 0, V 0, K 1 are there
+      // the first scores need K tile 0 only: the loads of the one or two tiles issued after it (at least PER - 1 per wave and
+      // tile) may still be in flight at the first barrier
+      if (nt > 1) dma_wait_keep<2 * (DmaMap<D, 4>::PER - 1)>();
+      else dma_wait_keep<DmaMap<D, 4>::PER - 1>();
+      __syncthreads();  // K tile 0 is there
+      dma_wait();       // V tile 0 and K tile 1, before the first step's barrier
       for (int jt = 0; jt < nt; ++jt) {
         __syncthreads();  // top of step jt: K tile jt and V tile jt-1 are free
         if (jt + 2 < nt) fetch(k + base, Kst, jt + 2);
