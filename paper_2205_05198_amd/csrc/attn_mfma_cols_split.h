@@ -8,19 +8,16 @@
 // registers, and the halves use different units:
 //   producer (waves 0..3)  S^T = K Q^T and dD^T = V dO^T with K and V operands held in registers, then the vector arithmetic:
 //                          P = exp2(alpha log2e S - LSE), Philox mask, D = M P / (1-p), dS = P (dD M / (1-p) - delta); the two
-//                          results go, rounded to bf16 and one query row per lane, to an exchange buffer in LDS (and, WDS, dS to
-//                          the tiles that the dQ product reads);
-//   consumer (waves 4..7)  moves them to the one-key-per-lane layout (identity matrix instructions), accumulates
-//                          dV^T += dO^T D and dK^T += Q^T dS, and issues every direct-to-LDS load of the workgroup.
+//                          results go, rounded to bf16, as row-major [32 rows][32 keys] tiles to an exchange buffer in LDS
+//                          (and, WDS, dS to the tiles that the dQ product reads);
+//   consumer (waves 4..7)  reads them one key per lane (transposing LDS reads), accumulates dV^T += dO^T D and
+//                          dK^T += Q^T dS, and issues every direct-to-LDS load of the workgroup.
 // The consumer works one tile behind the producer; (Q, dO) tiles live in three stages: tile m is loaded during step m-1, read
 // by the producer in step m and by the consumer in step m+1.  One workgroup barrier per step.
 // Needs s % 64 == 0.  Everything is in vector registers (compiled with -amdgpu-mfma-vgpr-form): no copies out of
 // accumulation registers.
 #pragma once
 #include "attn_mfma_cols_kernel.h"
-#ifndef SAR_EXP
-#define SAR_EXP 0
-#endif
 
 namespace sar {
 
@@ -32,7 +29,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   constexpr int BN = 64, BI = 64, KP = D + 8, KC = D / 16, DT = D / 32, NST = 3;
   constexpr int TILE = 64 * KP;
   __shared__ __attribute__((aligned(16))) uint16_t smem[2 * NST * TILE];  // stage s: Q at 2 s TILE, dO at (2 s + 1) TILE; afterwards the epilogue's buffers
-  __shared__ __attribute__((aligned(16))) uint16_t xb[2][4][4][512];      // exchange: [step parity][wave pair][D c0, D c1, dS c0, dS c1][16 bytes per lane]
+  __shared__ __attribute__((aligned(16))) uint16_t xb[2][4][4][512];      // exchange: [step parity][wave pair][D rows 0..15, D rows 16..31, dS likewise][16 rows x 32 keys]
   __shared__ float lse_s[NST][BI], delta_s[NST][BI];
 
   const int N = P.b * P.A;
@@ -49,10 +46,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   const int it0 = P.causal ? kb : 0;
   const uint16_t* qg = q + base;
   const uint16_t* dog = dO + base;
-#if SAR_EXP == 46
-  const uint64_t R_in = __builtin_amdgcn_s_memrealtime();
-  uint64_t R_first = 0, R_loop = 0;
-#endif
 
   if (producer) {
     // ---- K and V operands of this wave's 32 keys, for the whole kernel: lane li holds key jw0 + perm_row(li).  They come
@@ -87,9 +80,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     }
     for (int m = it0; m <= nit; ++m) {
       __syncthreads();  // tile m is in its stage; the consumer has read exchange buffer m & 1 (tile m - 2)
-#if SAR_EXP == 46
-      if (m == it0) R_first = __builtin_amdgcn_s_memrealtime();
-#endif
       if (m == nit) break;
       const uint16_t* Qs = smem + (m % NST) * 2 * TILE;
       const uint16_t* qrow = Qs + (32 * is + li) * KP + 8 * hh;
@@ -175,15 +165,16 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         ds_tile += ds_step;
         if (P.causal) ds_step += kDsTileElems;
       }
-      bf16x8_t* x = reinterpret_cast<bf16x8_t*>(&xb[m & 1][w][0][0]) + lane;
-      x[0] = df[0];
-      x[64] = df[1];
-      x[128] = dsf[0];
-      x[192] = dsf[1];
+      // exchange tiles [32 rows][32 keys], 64 bytes per row; the 16-byte piece q of row r sits at piece q ^ 2 (r>>2 & 1), which
+      // spreads the writes of a wave over all banks
+      uint16_t* x = &xb[m & 1][w][0][0] + 32 * li;
+      const int sw = 2 * ((li >> 2) & 1);
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        *reinterpret_cast<bf16x8_t*>(x + 8 * ((2 * c + hh) ^ sw)) = df[c];
+        *reinterpret_cast<bf16x8_t*>(x + 1024 + 8 * ((2 * c + hh) ^ sw)) = dsf[c];
+      }
     }
-#if SAR_EXP == 46
-    R_loop = __builtin_amdgcn_s_memrealtime();
-#endif
     // the barriers of the consumers' epilogue
     __syncthreads();
     __syncthreads();
@@ -207,15 +198,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     for (int r = 0; r < NR; ++r) fetch(it0, r);
     if (w == 0) fetch_stats(it0);
     __syncthreads();  // the producers have staged K and V (they read them before the first barrier of the loop)
-    // identity operands: ident[c] has a one where this lane's column li equals key 16*c + 8*hh + e
-    bf16x8_t ident[2];
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      union { uint16_t h[8]; bf16x8_t v; } u;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) u.h[e] = (li == 16 * c + 8 * hh + e) ? (uint16_t)0x3F80 : (uint16_t)0;
-      ident[c] = u.v;
-    }
     float16_t dkacc[DT], dvacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -237,18 +219,24 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       const int t = m - 1;
       const uint16_t* Qs = smem + (t % NST) * 2 * TILE;
       const uint16_t* dOs = Qs + TILE;
-      const bf16x8_t* x = reinterpret_cast<const bf16x8_t*>(&xb[t & 1][w][0][0]) + lane;
-      const bf16x8_t df0 = x[0], df1 = x[64], ds0 = x[128], ds1 = x[192];
-      // one-key-per-lane copies: T[i][key] = sum_k tile[i][k] I[k][key]
-      float16_t tD, tS;
+      // one-key-per-lane operands straight from the exchange tiles (transposing LDS reads): slot e of lane (li, hh) <-> key li,
+      // row 16 X + 8 (e>>2) + 4 hh + (e&3), the row order of the transposed Q / dO operands
+      bf16x8_t dT[2], sT[2];
+      {
+        const int lam = lane & 15, blk = lane >> 4;
+        const uint16_t* xp = &xb[t & 1][w][0][0] + (4 * (blk >> 1) + (lam >> 2)) * 32 + 8 * ((2 * (blk & 1) + ((lam & 3) >> 1)) ^ (2 * (blk >> 1))) + 4 * (lam & 1);
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { tD[e] = 0.f; tS[e] = 0.f; }
-      tD = mfma32(df0, ident[0], tD);
-      tS = mfma32(ds0, ident[0], tS);
-      tD = mfma32(df1, ident[1], tD);
-      tS = mfma32(ds1, ident[1], tS);
+        for (int X = 0; X < 2; ++X) {
+          union { short4_t h[2]; bf16x8_t v; } ud, us;
+          ud.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X));
+          ud.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X + 256));
+          us.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 1024 + 512 * X));
+          us.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 1024 + 512 * X + 256));
+          dT[X] = ud.v;
+          sT[X] = us.v;
+        }
+      }
       if (more) { fetch(m + 1, 0); fetch(m + 1, 1); }
-      // acc[4g + r] <-> row 8g + 4hh + r: operand X takes g in {2X, 2X+1}, i.e. rows 16X + 8*(e>>2) + 4hh + (e&3)
       constexpr int kAhead = 2, NP = 2 * DT;
       bf16x8_t oa[kAhead], qa[kAhead];
       auto tr = [&](const uint16_t* tile, int p) __attribute__((always_inline)) {
@@ -256,15 +244,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       };
 #pragma unroll
       for (int a = 0; a < kAhead; ++a) oa[a] = tr(dOs, a), qa[a] = tr(Qs, a);
-      bf16x8_t dT[2], sT[2];
-#pragma unroll
-      for (int X = 0; X < 2; ++X) {
-        float td[8], ts[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { td[e] = tD[8 * X + e]; ts[e] = tS[8 * X + e]; }
-        dT[X] = pack8(td);
-        sT[X] = pack8(ts);
-      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
@@ -296,12 +275,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   // all eight waves: the producers' threads copy dK out, the consumers' dV
   if (tid < 256) lds_rows_to_global<D>(smem + 4 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
   else lds_rows_to_global<D>(smem + 5 * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid - 256);
-#if SAR_EXP == 46
-  if (tid == 0) {
-    uint64_t* dbg = reinterpret_cast<uint64_t*>(ds_ws + (int64_t)N * ds_tiles_per_head(P) * kDsTileElems) + (size_t)blockIdx.x * 8;
-    dbg[0] = R_in; dbg[1] = R_first; dbg[2] = R_loop; dbg[3] = __builtin_amdgcn_s_memrealtime(); dbg[4] = nit - it0;
-  }
-#endif
 }
 
 }  // namespace sar
