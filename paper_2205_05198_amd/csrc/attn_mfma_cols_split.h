@@ -10,8 +10,9 @@
 //                          P = exp2(alpha log2e S - LSE), Philox mask, D = M P / (1-p), dS = P (dD M / (1-p) - delta); the two
 //                          results go, rounded to bf16, as row-major [32 rows][32 keys] tiles to an exchange buffer in LDS
 //                          (and, WDS, dS to the tiles that the dQ product reads);
-//   consumer (waves 4..7)  reads them one key per lane (transposing LDS reads), accumulates dV^T += dO^T D and
-//                          dK^T += Q^T dS, and issues every direct-to-LDS load of the workgroup.
+//   consumer (waves 4..7)  reads them one key per lane (transposing LDS reads) and accumulates dV^T += dO^T D (two of the
+//                          waves, one per 32 keys, over all 64 rows of the tile) or dK^T += Q^T dS (the other two), and
+//                          issues every direct-to-LDS load of the workgroup.
 // The consumer works one tile behind the producer; (Q, dO) tiles live in three stages: tile m is loaded during step m-1, read
 // by the producer in step m and by the consumer in step m+1.  One workgroup barrier per step.
 // Needs s % 64 == 0.  Everything is in vector registers (compiled with -amdgpu-mfma-vgpr-form): no copies out of
@@ -178,7 +179,6 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     // the barriers of the consumers' epilogue
     __syncthreads();
     __syncthreads();
-    __syncthreads();
   } else {
     // ---- consumer ----
     DmaMap<D> map;
@@ -198,11 +198,17 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     for (int r = 0; r < NR; ++r) fetch(it0, r);
     if (w == 0) fetch_stats(it0);
     __syncthreads();  // the producers have staged K and V (they read them before the first barrier of the loop)
-    float16_t dkacc[DT], dvacc[DT];
+    // Consumer w = (kgp, role): role 0 accumulates dV^T of the pair of producers with key group kgp (both row halves of the
+    // tile) from D and dO, role 1 dK^T from dS and Q.  One accumulator set per wave, complete at the end: no merging.
+    const int role = is;
+    float16_t acc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { dkacc[dt][e] = 0.f; dvacc[dt][e] = 0.f; }
+      for (int e = 0; e < 16; ++e) acc[dt][e] = 0.f;
+    // this lane's address inside a [32 rows][32 keys] exchange tile for the transposing read of rows 0..3 / 4..7 (hh)
+    const int lam = lane & 15, blk = lane >> 4;
+    const int xoff = 1024 * role + (4 * (blk >> 1) + (lam >> 2)) * 32 + 8 * ((2 * (blk & 1) + ((lam & 3) >> 1)) ^ (2 * (blk >> 1))) + 4 * (lam & 1);
 
     for (int m = it0; m <= nit; ++m) {
       dma_wait();       // this wave's share of tile m has landed
@@ -217,59 +223,43 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         continue;
       }
       const int t = m - 1;
-      const uint16_t* Qs = smem + (t % NST) * 2 * TILE;
-      const uint16_t* dOs = Qs + TILE;
+      const uint16_t* Ts = smem + (t % NST) * 2 * TILE + (role ? 0 : TILE);  // Q for dK, dO for dV
       // one-key-per-lane operands straight from the exchange tiles (transposing LDS reads): slot e of lane (li, hh) <-> key li,
-      // row 16 X + 8 (e>>2) + 4 hh + (e&3), the row order of the transposed Q / dO operands
-      bf16x8_t dT[2], sT[2];
-      {
-        const int lam = lane & 15, blk = lane >> 4;
-        const uint16_t* xp = &xb[t & 1][w][0][0] + (4 * (blk >> 1) + (lam >> 2)) * 32 + 8 * ((2 * (blk & 1) + ((lam & 3) >> 1)) ^ (2 * (blk >> 1))) + 4 * (lam & 1);
+      // row 32 h + 16 X + 8 (e>>2) + 4 hh + (e&3), the row order of the transposed Q / dO operands
+      bf16x8_t bT[2][2];  // [row half h][X]
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint16_t* xp = &xb[t & 1][2 * h + kgp][0][0] + xoff;
 #pragma unroll
         for (int X = 0; X < 2; ++X) {
-          union { short4_t h[2]; bf16x8_t v; } ud, us;
-          ud.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X));
-          ud.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X + 256));
-          us.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 1024 + 512 * X));
-          us.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 1024 + 512 * X + 256));
-          dT[X] = ud.v;
-          sT[X] = us.v;
+          union { short4_t q[2]; bf16x8_t v; } u;
+          u.q[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X));
+          u.q[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_t*)(xp + 512 * X + 256));
+          bT[h][X] = u.v;
         }
       }
       if (more) { fetch(m + 1, 0); fetch(m + 1, 1); }
-      constexpr int kAhead = 2, NP = 2 * DT;
-      bf16x8_t oa[kAhead], qa[kAhead];
-      auto tr = [&](const uint16_t* tile, int p) __attribute__((always_inline)) {
-        return ld_frag_tr_perm(tile, KP, 32 * is + 16 * (p / DT), 32 * (p % DT), lane);
+      constexpr int kAhead = 3, NP = 4 * DT;
+      bf16x8_t ta[kAhead];
+      auto tr = [&](int p) __attribute__((always_inline)) {  // product p: rows 16 (p / DT) .. + 15 of the tile, columns 32 (p % DT) ..
+        return ld_frag_tr_perm(Ts, KP, 16 * (p / DT), 32 * (p % DT), lane);
       };
 #pragma unroll
-      for (int a = 0; a < kAhead; ++a) oa[a] = tr(dOs, a), qa[a] = tr(Qs, a);
+      for (int a = 0; a < kAhead; ++a) ta[a] = tr(a);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int p = 0; p < NP; ++p) {
-        dvacc[p % DT] = mfma32(oa[p % kAhead], dT[p / DT], dvacc[p % DT]);
-        dkacc[p % DT] = mfma32(qa[p % kAhead], sT[p / DT], dkacc[p % DT]);
-        if (p + kAhead < NP) oa[p % kAhead] = tr(dOs, p + kAhead), qa[p % kAhead] = tr(Qs, p + kAhead);
-        // the rest of the next tile's loads, dealt out between the products
+        acc[p % DT] = mfma32(ta[p % kAhead], bT[p / (2 * DT)][(p / DT) & 1], acc[p % DT]);
+        if (p + kAhead < NP) ta[p % kAhead] = tr(p + kAhead);
+        // the rest of the next tile's loads, one after each of the first products: they have the rest of the step to land
         if (more && 2 + p < NR) fetch(m + 1, 2 + p);
         __builtin_amdgcn_sched_barrier(0);
       }
-      static_assert(NR - 2 <= NP, "more load rounds than pairs of products");
+      static_assert(NR - 2 <= NP, "more load rounds than products");
     }
-    // ---- sum the two row halves, scale, store ----
-    __syncthreads();
-    // each wave of a pair gives one accumulator set away and finishes the other: the upper half completes dV, the lower dK
-    float* mg = reinterpret_cast<float*>(smem) + kgp * (64 * 32 * DT);
-    if (is == 1) acc_put<DT>(mg, dkacc, lane);
-    else acc_put<DT>(mg + 16 * DT * 64, dvacc, lane);
-    __syncthreads();
-    if (is == 0) {
-      acc_combine<DT>(mg, dkacc, 1.f, 1.f, lane);
-      acc_to_lds_rows<DT>(smem + 4 * TILE, KP, 32 * kgp + li, dkacc, P.scale, hh);
-    } else {
-      acc_combine<DT>(mg + 16 * DT * 64, dvacc, 1.f, 1.f, lane);
-      acc_to_lds_rows<DT>(smem + 5 * TILE, KP, 32 * kgp + li, dvacc, 1.0f, hh);
-    }
+    // ---- scale, round, rows through LDS ----
+    __syncthreads();  // every consumer is done with the last tile (the output tiles overlap its stage)
+    acc_to_lds_rows<DT>(smem + (role ? 4 : 5) * TILE, KP, 32 * kgp + li, acc, role ? P.scale : 1.0f, hh);
     __syncthreads();
   }
   // all eight waves: the producers' threads copy dK out, the consumers' dV
