@@ -266,7 +266,9 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
  * (every variant computes the same result).  Each argument: -1 = the library's choice, 0 = off, 1 = on.
  *   fwd_128_rows      forward with 128 instead of 64 query rows per workgroup (needs s >= 128)
  *   fwd_loader_waves  forward (64-row workgroups) with four extra waves that only fetch K / V tiles (1), or as producer /
- *                     consumer wave pairs (2: one wave computes scores and softmax, the other accumulates P V and fetches)
+ *                     consumer wave pairs (2: one wave computes scores and softmax, the other accumulates P V and fetches),
+ *                     or 3: as 1 with persistent workgroups, each working through a list of row blocks (used only when
+ *                     b x heads does not exceed the number of compute units; otherwise 3 behaves as 1)
  *   dq_loader_waves   the same for the row pass of the recompute-twice backward
  *   dkdv_pipelined    form of the column pass where s % 64 == 0: 0 plain; 1 software-pipelined (head dimension 128 and 160
  *                     only: score tiles of the next query tile computed beside this tile's vector arithmetic); 2 producer /

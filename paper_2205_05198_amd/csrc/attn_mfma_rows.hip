@@ -26,6 +26,7 @@
 #include <atomic>
 #include <type_traits>
 #include "attn_mfma_fwd_split.h"
+#include "attn_mfma_fwd_pers.h"
 
 namespace sar {
 
@@ -602,7 +603,23 @@ static hipError_t fwd_d(const AttnParams& P, const void* q, const void* k, const
                            (const uint16_t*)v, (uint16_t*)o, lse);
       return hipGetLastError();
     }
-    const bool use_lw = (lw == 0 || lw == 1) ? lw == 1 : D != 96;
+    const bool use_lw = (lw == 0 || lw == 1 || lw == 3) ? lw != 0 : D != 96;
+    // persistent form of the same kernel (each workgroup works through a list of row blocks and overlaps a block's start with
+    // the end of the one before): needs a grid of (row blocks at a time) x (heads) within the CU count; chosen when every
+    // workgroup then gets at least two row blocks (measured at s = 2048: 16 heads of 160 -5 % .. -2.5 %; 12 heads of 128, where
+    // 21 of the 32 blocks of a head start at once and only some workgroups get a second one, +1 %); forced by 3
+    const int cus = cu_count();
+    const bool pers = use_lw && N <= cus && (lw == 3 || (lw < 0 && nrb >= 2 * std::min(nrb, cus / N)));
+    if (pers) {
+      const int R = std::min(nrb, cus / N);
+      if (P.thresh != 0)
+        hipLaunchKernelGGL((attn_fwd_pers_kernel<D, true>), dim3((unsigned)(R * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (uint16_t*)o, lse);
+      else
+        hipLaunchKernelGGL((attn_fwd_pers_kernel<D, false>), dim3((unsigned)(R * N)), dim3(512), 0, st, P, (const uint16_t*)q, (const uint16_t*)k,
+                           (const uint16_t*)v, (uint16_t*)o, lse);
+      return hipGetLastError();
+    }
     if (use_lw) {
       if (P.thresh != 0)
         hipLaunchKernelGGL((attn_fwd_mfma_kernel<D, true, 2, true>), dim3((unsigned)(nrb * N)), dim3(512), 0, st, P, (const uint16_t*)q,

@@ -154,6 +154,23 @@ def test_forward_with_and_without_loader_waves(d, s, causal, lw):
     _check_bf16_heads(f"fwd-lw{lw}", sh, q, k, v, do, got, range(2))
 
 
+@pytest.mark.parametrize("d,s,b,A,causal", [(160, 328, 3, 44, 1), (128, 776, 1, 44, 1), (160, 264, 2, 66, 0)])
+def test_forward_persistent_workgroups(d, s, b, A, causal):
+    """The forward with persistent workgroups (forced), at head counts where a workgroup really gets several row blocks: 132
+    heads (one workgroup per head takes all its row blocks in turn) and 44 heads (five workgroups per head: ranks wq, 9 - wq,
+    10 + wq of 13 row blocks, the last one ragged).  A later block of a list starts from Q operands, Philox words and K / V
+    tiles requested during the block before it."""
+    import paper_2205_05198_amd as sar
+    from gpu_util import run_attn
+    sar.sar_test_force_variants(0, 3, -1, -1)
+    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=0.1, seed=77, offset=(1 << 32) - 12345, causal=causal)
+    q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=31)
+    print(f"fwd persistent d={d} s={s} b={b} A={A} causal={causal}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do)
+    N = b * A
+    _check_bf16_heads("fwd-pers", sh, q, k, v, do, got, [0, 1, N // 2, N - 1])
+
+
 @pytest.mark.parametrize("two_pass", [False, True])
 @pytest.mark.parametrize("d,s,causal", [(160, 8, 1), (64, 24, 1), (128, 64, 1), (160, 72, 1), (96, 40, 0), (160, 56, 0)])
 def test_bf16_matrix_core_path_short_sequences(d, s, causal, two_pass):
@@ -182,7 +199,7 @@ def test_random_shapes_and_kernel_variants():
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = [rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2]), rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2])]
+        env = [rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2, 3]), rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2])]
         if s < 128:
             env[0] = -1
         sar.sar_test_force_variants(*env)

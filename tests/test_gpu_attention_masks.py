@@ -104,7 +104,8 @@ def test_fused_kernel_masks_small(d, s, causal):
 
 
 def test_fused_kernel_masks_kernel_variants():
-    """The forward's other variants (128-row workgroups; without loader waves) and both forms of the column pass draw the same mask."""
+    """The forward's other variants (128-row workgroups; without loader waves; producer / consumer pairs; persistent workgroups)
+    and the forms of the column pass draw the same mask."""
     sh = oracle.AttnShape(s=328, b=1, a=4, h=4 * 160, t=2, rank=1, p=0.25, seed=99, offset=12345)
     try:
         for variant in ((1, -1, -1, -1), (0, 0, 0, -1), (0, 1, 1, -1), (0, 2, -1, -1)):
@@ -112,6 +113,10 @@ def test_fused_kernel_masks_kernel_variants():
             print(f"masks variants={variant}", flush=True)
             _compare(sh, "fwd")
             _compare(sh, "dq", two_pass=True)
+        # the forward with persistent workgroups, 132 heads: every workgroup takes the three row blocks of its head in turn
+        sar.sar_test_force_variants(0, 3, -1, -1)
+        print("masks persistent forward", flush=True)
+        _compare(oracle.AttnShape(s=328, b=3, a=44, h=44 * 160, p=0.25, seed=99, offset=(1 << 32) - 70000), "fwd")
         # the column pass in its three forms at a length of full tiles (s % 64 == 0), every head dimension (a form that does not
         # exist at a head dimension falls back to the plain one)
         for d in (64, 96, 128, 160):
