@@ -272,7 +272,9 @@ sar_status bias_gelu_bwd(const sar_rows_desc* desc, const void* dy, const void* 
  *   dq_loader_waves   the same for the row pass of the recompute-twice backward
  *   dkdv_pipelined    form of the column pass where s % 64 == 0: 0 plain; 1 software-pipelined (head dimension 128 and 160
  *                     only: score tiles of the next query tile computed beside this tile's vector arithmetic); 2 producer /
- *                     consumer (two waves per SIMD: one computes scores, softmax, mask and dS, the other accumulates dK, dV)
+ *                     consumer (two waves per SIMD: one computes scores, softmax, mask and dS, the other accumulates dK, dV),
+ *                     one key block per workgroup; 3 the same with persistent workgroups that each take several key blocks
+ *                     (only when b x heads does not exceed the number of compute units; otherwise 3 behaves as 2)
  * Process-wide; not meant to be changed while another thread launches.
  */
 void sar_test_force_variants(int fwd_128_rows, int fwd_loader_waves, int dq_loader_waves, int dkdv_pipelined);

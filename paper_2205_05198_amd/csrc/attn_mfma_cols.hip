@@ -8,16 +8,17 @@
 namespace sar {
 
 // form of the column pass at d = 128, 160 and s % 64 == 0: -1 = the library's choice; 0 plain, 1 software-pipelined,
-// 2 producer / consumer waves (forced forms fall back to the plain one where they do not exist)
+// 2 producer / consumer waves, 3 the same with persistent workgroups (forced forms fall back where they do not exist: 1 to
+// the plain one, 3 to 2)
 static std::atomic<int> g_force_form{-1};
 void attn_mfma_force_dkdv_pipelined(int force) { g_force_form = force; }
 
 hipError_t launch_attn_bwd_dkdv_mfma_small(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
                                            const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);  // attn_mfma_cols_small.hip
 hipError_t launch_attn_bwd_dkdv_mfma_split(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
-                                           const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st);  // attn_mfma_cols_split.hip
+                                           const float* delta, void* dk, void* dv, uint16_t* ds_ws, int pers, hipStream_t st);  // attn_mfma_cols_split.hip
 
-// the form that runs: 0 plain, 1 software-pipelined, 2 producer / consumer
+// the form that runs: 0 plain, 1 software-pipelined, 2 producer / consumer (3: forced persistent)
 template <int D>
 static int dkdv_form(const AttnParams& P, const uint16_t* ds_ws) {
   if (P.s % 64 != 0) return 0;
@@ -29,24 +30,32 @@ static int dkdv_form(const AttnParams& P, const uint16_t* ds_ws) {
   return 2;
 }
 
+// persistent workgroups in the producer / consumer form: -1 the launcher decides by shape, 0 / 1 forced
+static int split_pers() {
+  const int force = g_force_form.load();
+  return force == 2 ? 0 : force == 3 ? 1 : -1;
+}
+
 hipError_t launch_attn_bwd_dkdv_mfma(const AttnParams& P, const void* q, const void* k, const void* v, const float* lse, const void* dO,
                                      const float* delta, void* dk, void* dv, uint16_t* ds_ws, hipStream_t st) {
   switch (P.d) {
     case 64:
-      if (dkdv_form<64>(P, ds_ws) == 2) return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+      if (dkdv_form<64>(P, ds_ws) >= 2) return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, split_pers(), st);
       return launch_attn_bwd_dkdv_mfma_small(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     case 96:
-      if (dkdv_form<96>(P, ds_ws) == 2) return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+      if (dkdv_form<96>(P, ds_ws) >= 2) return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, split_pers(), st);
       return launch_attn_bwd_dkdv_mfma_small(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
     case 128:
       switch (dkdv_form<128>(P, ds_ws)) {
-        case 2: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        case 2:
+        case 3: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, split_pers(), st);
         case 1: return bwd_dkdv_pipe_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
         default: return bwd_dkdv_d<128>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
       }
     case 160:
       switch (dkdv_form<160>(P, ds_ws)) {
-        case 2: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
+        case 2:
+        case 3: return launch_attn_bwd_dkdv_mfma_split(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, split_pers(), st);
         case 1: return bwd_dkdv_pipe_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
         default: return bwd_dkdv_d<160>(P, q, k, v, lse, dO, delta, dk, dv, ds_ws, st);
       }

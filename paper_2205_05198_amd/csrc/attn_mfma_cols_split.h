@@ -22,7 +22,7 @@
 
 namespace sar {
 
-template <int D, bool DROP, bool WDS>
+template <int D, bool DROP, bool WDS, bool PERS = false>
 __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams P, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                                                                     const uint16_t* __restrict__ v, const float* __restrict__ lse,
                                                                     const uint16_t* __restrict__ dO, const float* __restrict__ delta,
@@ -34,7 +34,15 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   __shared__ float lse_s[NST][BI], delta_s[NST][BI];
 
   const int N = P.b * P.A;
-  const int kb = (int)(blockIdx.x / N);  // key block 0 sweeps the most rows: heaviest first
+  const int nb = P.s / BN;
+  // Which key blocks this workgroup takes.  Plain: one, block blockIdx / N (key block 0 sweeps the most rows: heaviest
+  // first).  PERS: the grid is R x N workgroups (R x N <= number of CUs) and workgroup (wq, head) takes its head's key blocks
+  // wq, 2R-1-wq, 2R+wq, 4R-1-wq, ...: a heavy block, then a light one; the next block's K, V and first (Q, dO) tile are
+  // requested during the last step of the block before and land while its epilogue runs.
+  const int Rr = PERS ? (int)gridDim.x / N : nb;
+  const int wq = (int)(blockIdx.x / N);
+  auto block_of = [&](const int j) __attribute__((always_inline)) { return (j & 1) ? (j + 1) * Rr - 1 - wq : j * Rr + wq; };  // >= nb: none
+  int kb = wq;
   const int bn = blockIdx.x % N, beta = bn / P.A, n = bn % P.A;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, li = lane & 31, hh = lane >> 5;
   const bool producer = wave < 4;
@@ -42,9 +50,13 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
   const int kgp = w & 1, is = w >> 1;
   const int64_t base = (int64_t)beta * P.stride_b + (int64_t)n * P.stride_a;
   const int gstride = (int)P.stride_s;
-  const int jw0 = kb * BN + kgp * 32;  // first key of this pair
+  int jw0 = kb * BN + kgp * 32;  // first key of this pair
   const int nit = P.s / BI;
-  const int it0 = P.causal ? kb : 0;
+  int it0 = P.causal ? kb : 0;
+  // (Q, dO) tile m of the current key block lives in stage (m - it0 + off) % NST; its K and V blocks are staged where tile
+  // it0 + 1 will go; its output tiles go where its last tile was
+  int off = 0;
+  auto stage_of = [&](const int m) __attribute__((always_inline)) { return (m - it0 + off) % NST; };
   const uint16_t* qg = q + base;
   const uint16_t* dog = dO + base;
 
@@ -53,15 +65,21 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     // through LDS (coalesced direct loads into the stage that tile it0 + 1 will take; rows swapped inside groups of 32):
     // fetched straight into registers, every lane reads 20 separate 16-byte pieces of its own row ----
     bf16x8_t kf[KC], vf[KC];
+    DmaMap<D> kvmap;
+    kvmap.init(w, lane, gstride, true);
     {
-      DmaMap<D> kvmap;
-      kvmap.init(w, lane, gstride, true);
-      uint16_t* Kst = smem + ((it0 + 1) % NST) * 2 * TILE;
+      uint16_t* Kst = smem + stage_of(it0 + 1) * 2 * TILE;
       dma_tile<D>(kvmap, k + base + (int64_t)(kb * BN) * gstride, Kst, w);
       dma_tile<D>(kvmap, v + base + (int64_t)(kb * BN) * gstride, Kst + TILE, w);
       dma_wait();
       __syncthreads();  // the K and V blocks are staged
-      const uint16_t* kw = Kst + (32 * kgp + li) * KP + 8 * hh;
+    }
+    const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
+    const float sc2 = P.scale * kLog2e;
+    const float log2_keep_scale = __builtin_amdgcn_logf(P.keep_scale), inv_keep_scale = 1.0f / P.keep_scale;  // v_log_f32 is log2
+    for (int j = 0;; ++j) {  // key blocks of this workgroup
+    {
+      const uint16_t* kw = smem + stage_of(it0 + 1) * 2 * TILE + (32 * kgp + li) * KP + 8 * hh;
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) {
         kf[kc] = ld_frag(kw + 16 * kc);
@@ -70,9 +88,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
 #pragma unroll
       for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(kf[kc]), "+v"(vf[kc]));  // read before the barrier that frees the stage
     }
-    const uint64_t headG = P.offset + (((uint64_t)beta * (uint64_t)P.a_global + (uint64_t)(P.head0 + n)) * (uint64_t)P.s) * (uint64_t)(P.s >> 3);
-    const float sc2 = P.scale * kLog2e;
-    const float log2_keep_scale = __builtin_amdgcn_logf(P.keep_scale), inv_keep_scale = 1.0f / P.keep_scale;  // v_log_f32 is log2
+    const int kb_n = PERS ? block_of(j + 1) : nb;
+    const bool has_next = kb_n < nb;
     uint16_t* ds_tile = nullptr;  // uniform: the wave's 2 KB of the dS tile (it, kb)
     int64_t ds_step = 0;
     if constexpr (WDS) {
@@ -82,7 +99,8 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     for (int m = it0; m <= nit; ++m) {
       __syncthreads();  // tile m is in its stage; the consumer has read exchange buffer m & 1 (tile m - 2)
       if (m == nit) break;
-      const uint16_t* Qs = smem + (m % NST) * 2 * TILE;
+      const int sg = stage_of(m);
+      const uint16_t* Qs = smem + sg * 2 * TILE;
       const uint16_t* qrow = Qs + (32 * is + li) * KP + 8 * hh;
       const uint16_t* drow = qrow + TILE;
       float16_t st, dd;
@@ -90,7 +108,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       for (int e = 0; e < 16; ++e) { st[e] = 0.f; dd[e] = 0.f; }
       const int i = m * BI + 32 * is + li;
       // lse2q: the row's LSE in log2 units minus log2 of 1/(1-p); dlq: delta (1-p)
-      const float lse2q = lse_s[m % NST][32 * is + li] * kLog2e - log2_keep_scale, dlq = delta_s[m % NST][32 * is + li] * inv_keep_scale;
+      const float lse2q = lse_s[sg][32 * is + li] * kLog2e - log2_keep_scale, dlq = delta_s[sg][32 * is + li] * inv_keep_scale;
       // The wave's instructions are ordered by hand so that its matrix instructions always have vector work of the same
       // wave beside them:
       //   1. S^T = K Q^T            between its matrix instructions: the two Philox calls of the tile (indices only);
@@ -176,23 +194,40 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         *reinterpret_cast<bf16x8_t*>(x + 1024 + 8 * ((2 * c + hh) ^ sw)) = dsf[c];
       }
     }
-    // the barriers of the consumers' epilogue
-    __syncthreads();
-    __syncthreads();
+    // The consumers' last step and epilogue.  The stage of the last tile becomes the output tiles; of the other two, the
+    // one after it takes the next key block's first (Q, dO) tile (fetched by the consumers), the one after that its K and V.
+    const int so = stage_of(nit - 1);
+    if (has_next) {
+      uint16_t* Kst = smem + ((so + 2) % NST) * 2 * TILE;
+      dma_tile<D>(kvmap, k + base + (int64_t)(kb_n * BN) * gstride, Kst, w);
+      dma_tile<D>(kvmap, v + base + (int64_t)(kb_n * BN) * gstride, Kst + TILE, w);
+    }
+    __syncthreads();  // the consumers are done with the last tile
+    if (has_next) dma_wait();
+    __syncthreads();  // the output tiles are complete (and the next K and V blocks staged)
+    lds_rows_to_global<D>(smem + so * 2 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
+    if (!has_next) break;
+    kb = kb_n;
+    jw0 = kb * BN + kgp * 32;
+    off = (so + 1) % NST;  // before it0 changes: stage_of(new it0) = off
+    it0 = P.causal ? kb : 0;
+    }  // key blocks
   } else {
     // ---- consumer ----
     DmaMap<D> map;
     map.init(w, lane, gstride, false);
-    auto fetch = [&](int it, int round) __attribute__((always_inline)) {  // rounds 0 .. 2 PER - 1 of tile `it`
+    auto fetch_to = [&](int it, int round, int sg) __attribute__((always_inline)) {  // rounds 0 .. 2 PER - 1 of tile `it`, into stage sg
       constexpr int PER = DmaMap<D>::PER;
-      uint16_t* dst = smem + (it % NST) * 2 * TILE;
+      uint16_t* dst = smem + sg * 2 * TILE;
       if (round < PER) dma_one<D>(map, qg + (int64_t)(it * BI) * gstride, dst, w, round);
       else dma_one<D>(map, dog + (int64_t)(it * BI) * gstride, dst + TILE, w, round - PER);
     };
-    auto fetch_stats = [&](int it) __attribute__((always_inline)) {  // one float per row, straight into LDS
-      dma4(lse + (size_t)bn * P.s + it * BI + lane, lds_addr(lse_s[it % NST]));
-      dma4(delta + (size_t)bn * P.s + it * BI + lane, lds_addr(delta_s[it % NST]));
+    auto fetch_stats_to = [&](int it, int sg) __attribute__((always_inline)) {  // one float per row, straight into LDS
+      dma4(lse + (size_t)bn * P.s + it * BI + lane, lds_addr(lse_s[sg]));
+      dma4(delta + (size_t)bn * P.s + it * BI + lane, lds_addr(delta_s[sg]));
     };
+    auto fetch = [&](int it, int round) __attribute__((always_inline)) { fetch_to(it, round, stage_of(it)); };
+    auto fetch_stats = [&](int it) __attribute__((always_inline)) { fetch_stats_to(it, stage_of(it)); };
     constexpr int NR = 2 * DmaMap<D>::PER;
 #pragma unroll
     for (int r = 0; r < NR; ++r) fetch(it0, r);
@@ -202,14 +237,19 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
     // tile) from D and dO, role 1 dK^T from dS and Q.  One accumulator set per wave, complete at the end: no merging.
     const int role = is;
     float16_t acc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[dt][e] = 0.f;
     // this lane's address inside a [32 rows][32 keys] exchange tile for the transposing read of rows 0..3 / 4..7 (hh)
     const int lam = lane & 15, blk = lane >> 4;
     const int xoff = 1024 * role + (4 * (blk >> 1) + (lam >> 2)) * 32 + 8 * ((2 * (blk & 1) + ((lam & 3) >> 1)) ^ (2 * (blk >> 1))) + 4 * (lam & 1);
 
+    for (int j = 0;; ++j) {  // key blocks of this workgroup
+    const int kb_n = PERS ? block_of(j + 1) : nb;
+    const bool has_next = kb_n < nb;
+    const int it0_n = P.causal ? kb_n : 0;
+    const int so = stage_of(nit - 1);  // the last tile's stage, then the output tiles
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[dt][e] = 0.f;
     for (int m = it0; m <= nit; ++m) {
       dma_wait();       // this wave's share of tile m has landed
       __syncthreads();  // ... and everybody's; the producers have written exchange buffer (m - 1) & 1 and read tile m - 1
@@ -223,7 +263,7 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         continue;
       }
       const int t = m - 1;
-      const uint16_t* Ts = smem + (t % NST) * 2 * TILE + (role ? 0 : TILE);  // Q for dK, dO for dV
+      const uint16_t* Ts = smem + stage_of(t) * 2 * TILE + (role ? 0 : TILE);  // Q for dK, dO for dV
       // one-key-per-lane operands straight from the exchange tiles (transposing LDS reads): slot e of lane (li, hh) <-> key li,
       // row 32 h + 16 X + 8 (e>>2) + 4 hh + (e&3), the row order of the transposed Q / dO operands
       bf16x8_t bT[2][2];  // [row half h][X]
@@ -239,6 +279,11 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
         }
       }
       if (more) { fetch(m + 1, 0); fetch(m + 1, 1); }
+      if (PERS && m == nit && has_next) {  // the next key block's first (Q, dO) tile and row statistics, into the stage after this one
+#pragma unroll
+        for (int r = 0; r < NR; ++r) fetch_to(it0_n, r, (so + 1) % NST);
+        if (w == 0) fetch_stats_to(it0_n, (so + 1) % NST);
+      }
       constexpr int kAhead = 3, NP = 4 * DT;
       bf16x8_t ta[kAhead];
       auto tr = [&](int p) __attribute__((always_inline)) {  // product p: rows 16 (p / DT) .. + 15 of the tile, columns 32 (p % DT) ..
@@ -257,14 +302,17 @@ __global__ __launch_bounds__(512, 1) void attn_bwd_dkdv_split_kernel(AttnParams 
       }
       static_assert(NR - 2 <= NP, "more load rounds than products");
     }
-    // ---- scale, round, rows through LDS ----
-    __syncthreads();  // every consumer is done with the last tile (the output tiles overlap its stage)
-    acc_to_lds_rows<DT>(smem + (role ? 4 : 5) * TILE, KP, 32 * kgp + li, acc, role ? P.scale : 1.0f, hh);
+    // ---- scale, round, rows through LDS (the producers' threads copy dK out, the consumers' dV) ----
+    __syncthreads();  // every consumer is done with the last tile (the output tiles take its stage)
+    acc_to_lds_rows<DT>(smem + (2 * so + (role ? 0 : 1)) * TILE, KP, 32 * kgp + li, acc, role ? P.scale : 1.0f, hh);
     __syncthreads();
+    lds_rows_to_global<D>(smem + (2 * so + 1) * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid - 256);
+    if (!has_next) break;
+    kb = kb_n;
+    off = (so + 1) % NST;  // before it0 changes: the new first tile's stage
+    it0 = it0_n;
+    }  // key blocks
   }
-  // all eight waves: the producers' threads copy dK out, the consumers' dV
-  if (tid < 256) lds_rows_to_global<D>(smem + 4 * TILE, dk + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid);
-  else lds_rows_to_global<D>(smem + 5 * TILE, dv + base + (int64_t)(kb * BN) * P.stride_s, gstride, P.s - kb * BN, tid - 256);
 }
 
 }  // namespace sar

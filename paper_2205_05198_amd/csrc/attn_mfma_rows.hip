@@ -555,7 +555,7 @@ void attn_mfma_force_variants(int fwd128, int fwdlw, int dqlw) {
 }
 
 // compute units of the current device, asked once
-static int cu_count() {
+int attn_mfma_cu_count() {
   static std::atomic<int> cached{0};
   int n = cached.load();
   if (n > 0) return n;
@@ -564,6 +564,8 @@ static int cu_count() {
   cached = n;
   return n;
 }
+
+static int cu_count() { return attn_mfma_cu_count(); }
 
 static bool fwd_use_128(const AttnParams& P) {
   if (P.s < 128) return false;

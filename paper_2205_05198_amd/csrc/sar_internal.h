@@ -70,6 +70,7 @@ hipError_t launch_attn_bwd_once_mfma(const AttnParams& P, const void* q, const v
 // test hook: force kernel variants (-1 = the library's choice, 0 / 1 = off / on)
 void attn_mfma_force_variants(int fwd128, int fwdlw, int dqlw);
 void attn_mfma_force_dkdv_pipelined(int force);
+int attn_mfma_cu_count();  // compute units of the current device, asked once
 
 // rows.hip: LayerNorm forward/backward and bias-dropout-add on [rows, h]
 hipError_t launch_ln_fwd(const RowsParams& P, bool bf16, const void* x, const void* gamma, const void* beta, void* y, float* mean,

@@ -154,6 +154,24 @@ def test_forward_with_and_without_loader_waves(d, s, causal, lw):
     _check_bf16_heads(f"fwd-lw{lw}", sh, q, k, v, do, got, range(2))
 
 
+@pytest.mark.parametrize("two_pass", [False, True])
+@pytest.mark.parametrize("d,s,b,A,causal", [(160, 320, 3, 44, 1), (128, 768, 1, 44, 1), (64, 256, 2, 66, 0)])
+def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
+    """The producer / consumer column pass with persistent workgroups (forced), at head counts where a workgroup really gets
+    several key blocks: 132 heads (one workgroup per head takes all its key blocks in turn) and 44 heads (five workgroups per
+    head: key blocks wq, 9 - wq, 10 + wq of 12).  A later block of a list starts from K, V and a first (Q, dO) tile requested
+    during the last step of the block before it, in LDS stages that rotate from block to block."""
+    import paper_2205_05198_amd as sar
+    from gpu_util import run_attn
+    sar.sar_test_force_variants(-1, -1, -1, 3)
+    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=0.1, seed=78, offset=(1 << 32) - 54321, causal=causal)
+    q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=37)
+    print(f"column pass persistent d={d} s={s} b={b} A={A} causal={causal} two_pass={two_pass}", flush=True)
+    got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
+    N = b * A
+    _check_bf16_heads("cols-pers", sh, q, k, v, do, got, [0, 1, N // 2, N - 1])
+
+
 @pytest.mark.parametrize("d,s,b,A,causal", [(160, 328, 3, 44, 1), (128, 776, 1, 44, 1), (160, 264, 2, 66, 0)])
 def test_forward_persistent_workgroups(d, s, b, A, causal):
     """The forward with persistent workgroups (forced), at head counts where a workgroup really gets several row blocks: 132
@@ -199,7 +217,7 @@ def test_random_shapes_and_kernel_variants():
         b, A, t = rng.choice([1, 2]), rng.choice([1, 2, 3]), rng.choice([1, 2])
         rank = rng.randrange(t)
         p, causal = rng.choice([0.0, 0.1, 0.3]), rng.choice([0, 1, 1])
-        env = [rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2, 3]), rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2])]
+        env = [rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2, 3]), rng.choice([-1, 0, 1]), rng.choice([-1, 0, 1, 2, 3])]
         if s < 128:
             env[0] = -1
         sar.sar_test_force_variants(*env)
@@ -211,7 +229,7 @@ def test_random_shapes_and_kernel_variants():
         _check_bf16_heads(f"sweep{case}", sh, q, k, v, do, got, range(b * A))
 
 
-@pytest.mark.parametrize("pipe", [0, 1, 2])
+@pytest.mark.parametrize("pipe", [0, 1, 2, 3])
 @pytest.mark.parametrize("two_pass", [False, True])
 @pytest.mark.parametrize("d,s,b,A,p,causal", [(160, 320, 1, 2, 0.1, 1), (128, 256, 2, 1, 0.25, 1), (160, 192, 1, 2, 0.1, 0), (128, 64, 1, 2, 0.0, 1), (160, 128, 1, 1, 0.0, 0),
                                               (64, 320, 2, 1, 0.1, 1), (96, 192, 1, 2, 0.25, 0), (64, 64, 1, 1, 0.0, 1)])

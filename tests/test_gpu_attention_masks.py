@@ -117,11 +117,18 @@ def test_fused_kernel_masks_kernel_variants():
         sar.sar_test_force_variants(0, 3, -1, -1)
         print("masks persistent forward", flush=True)
         _compare(oracle.AttnShape(s=328, b=3, a=44, h=44 * 160, p=0.25, seed=99, offset=(1 << 32) - 70000), "fwd")
+        # the column pass with persistent workgroups, 132 heads: every workgroup takes the five key blocks of its head in turn
+        sar.sar_test_force_variants(-1, -1, -1, 3)
+        print("masks persistent column pass", flush=True)
+        shp = oracle.AttnShape(s=320, b=3, a=44, h=44 * 160, p=0.25, seed=99, offset=(1 << 32) - 70000)
+        for two_pass in (False, True):
+            _compare(shp, "dv", two_pass)
+        _compare(shp, "dq", False)
         # the column pass in its three forms at a length of full tiles (s % 64 == 0), every head dimension (a form that does not
         # exist at a head dimension falls back to the plain one)
         for d in (64, 96, 128, 160):
             sh2 = oracle.AttnShape(s=320, b=1, a=4, h=4 * d, t=2, rank=1, p=0.25, seed=99, offset=(1 << 32) - 4000)
-            for pipe in (0, 1, 2):
+            for pipe in (0, 1, 2, 3):
                 sar.sar_test_force_variants(-1, -1, -1, pipe)
                 print(f"masks column pass form={pipe} d={d}", flush=True)
                 for two_pass in (False, True):
