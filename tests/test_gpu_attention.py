@@ -155,12 +155,13 @@ def test_forward_with_and_without_loader_waves(d, s, causal, lw):
 
 
 @pytest.mark.parametrize("two_pass", [False, True])
-@pytest.mark.parametrize("d,s,b,A,causal", [(160, 320, 3, 44, 1), (128, 768, 1, 44, 1), (64, 256, 2, 66, 0)])
+@pytest.mark.parametrize("d,s,b,A,causal", [(160, 320, 3, 44, 1), (128, 768, 1, 44, 1), (64, 256, 2, 66, 0), (64, 128, 5, 60, 1)])
 def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
     """The producer / consumer column pass with persistent workgroups (forced), at head counts where a workgroup really gets
     several key blocks: 132 heads (one workgroup per head takes all its key blocks in turn) and 44 heads (five workgroups per
     head: key blocks wq, 9 - wq, 10 + wq of 12).  A later block of a list starts from K, V and a first (Q, dO) tile requested
-    during the last step of the block before it, in LDS stages that rotate from block to block."""
+    during the last step of the block before it, in LDS stages that rotate from block to block.  300 heads: more heads than
+    compute units, the request falls back to one key block per workgroup."""
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(-1, -1, -1, 3)
@@ -172,12 +173,13 @@ def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
     _check_bf16_heads("cols-pers", sh, q, k, v, do, got, [0, 1, N // 2, N - 1])
 
 
-@pytest.mark.parametrize("d,s,b,A,causal", [(160, 328, 3, 44, 1), (128, 776, 1, 44, 1), (160, 264, 2, 66, 0)])
+@pytest.mark.parametrize("d,s,b,A,causal", [(160, 328, 3, 44, 1), (128, 776, 1, 44, 1), (160, 264, 2, 66, 0), (128, 136, 5, 60, 1)])
 def test_forward_persistent_workgroups(d, s, b, A, causal):
     """The forward with persistent workgroups (forced), at head counts where a workgroup really gets several row blocks: 132
     heads (one workgroup per head takes all its row blocks in turn) and 44 heads (five workgroups per head: ranks wq, 9 - wq,
     10 + wq of 13 row blocks, the last one ragged).  A later block of a list starts from Q operands, Philox words and K / V
-    tiles requested during the block before it."""
+    tiles requested during the block before it.  300 heads: more heads than compute units, the request falls back to one
+    row block per workgroup."""
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(0, 3, -1, -1)
