@@ -155,8 +155,8 @@ def test_forward_with_and_without_loader_waves(d, s, causal, lw):
 
 
 @pytest.mark.parametrize("two_pass", [False, True])
-@pytest.mark.parametrize("d,s,b,A,causal", [(160, 320, 3, 44, 1), (128, 768, 1, 44, 1), (64, 256, 2, 66, 0), (64, 128, 5, 60, 1)])
-def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
+@pytest.mark.parametrize("d,s,b,A,causal,p", [(160, 320, 3, 44, 1, 0.1), (128, 768, 1, 44, 1, 0.1), (64, 256, 2, 66, 0, 0.1), (64, 128, 5, 60, 1, 0.1), (160, 384, 1, 132, 1, 0.0)])
+def test_column_pass_persistent_workgroups(d, s, b, A, causal, p, two_pass):
     """The producer / consumer column pass with persistent workgroups (forced), at head counts where a workgroup really gets
     several key blocks: 132 heads (one workgroup per head takes all its key blocks in turn) and 44 heads (five workgroups per
     head: key blocks wq, 9 - wq, 10 + wq of 12).  A later block of a list starts from K, V and a first (Q, dO) tile requested
@@ -165,7 +165,7 @@ def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(-1, -1, -1, 3)
-    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=0.1, seed=78, offset=(1 << 32) - 54321, causal=causal)
+    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=p, seed=78, offset=(1 << 32) - 54321, causal=causal)
     q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=37)
     print(f"column pass persistent d={d} s={s} b={b} A={A} causal={causal} two_pass={two_pass}", flush=True)
     got = run_attn(sh, "bf16", q, k, v, do, two_pass=two_pass)
@@ -173,8 +173,8 @@ def test_column_pass_persistent_workgroups(d, s, b, A, causal, two_pass):
     _check_bf16_heads("cols-pers", sh, q, k, v, do, got, [0, 1, N // 2, N - 1])
 
 
-@pytest.mark.parametrize("d,s,b,A,causal", [(160, 328, 3, 44, 1), (128, 776, 1, 44, 1), (160, 264, 2, 66, 0), (128, 136, 5, 60, 1)])
-def test_forward_persistent_workgroups(d, s, b, A, causal):
+@pytest.mark.parametrize("d,s,b,A,causal,p", [(160, 328, 3, 44, 1, 0.1), (128, 776, 1, 44, 1, 0.1), (160, 264, 2, 66, 0, 0.1), (128, 136, 5, 60, 1, 0.1), (160, 392, 1, 132, 1, 0.0)])
+def test_forward_persistent_workgroups(d, s, b, A, causal, p):
     """The forward with persistent workgroups (forced), at head counts where a workgroup really gets several row blocks: 132
     heads (one workgroup per head takes all its row blocks in turn) and 44 heads (five workgroups per head: ranks wq, 9 - wq,
     10 + wq of 13 row blocks, the last one ragged).  A later block of a list starts from Q operands, Philox words and K / V
@@ -183,7 +183,7 @@ def test_forward_persistent_workgroups(d, s, b, A, causal):
     import paper_2205_05198_amd as sar
     from gpu_util import run_attn
     sar.sar_test_force_variants(0, 3, -1, -1)
-    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=0.1, seed=77, offset=(1 << 32) - 12345, causal=causal)
+    sh = oracle.AttnShape(s=s, b=b, a=A, h=A * d, p=p, seed=77, offset=(1 << 32) - 12345, causal=causal)
     q, k, v, do = attn_inputs(s, b, A, d, "bf16", seed=31)
     print(f"fwd persistent d={d} s={s} b={b} A={A} causal={causal}", flush=True)
     got = run_attn(sh, "bf16", q, k, v, do)
